@@ -1,0 +1,170 @@
+/*
+ * optimus_attn.h - C ABI of the MI355X (gfx950) chunked block-diffusion
+ * attention library.
+ *
+ * The operation is the attention step of Optimus's elastic diffusion decoding
+ * (Sec. 4 "Streaming Chunked Decoding", Sec. 6 "Implementation"): in one
+ * decoding iteration each request i of a continuously batched set contributes
+ * a chunk of c_i query tokens (c_i is re-chosen every iteration by the elastic
+ * scheduler, Sec. 5); the chunk's K/V are mapped into the paged KV cache and
+ * the chunk attends to the request's cached tokens (all visible: earlier
+ * blocks and committed tokens of the current block, Sec. 2.3 / 4.2) and to
+ * itself bidirectionally (in-block streaming, Sec. 7.2).
+ *
+ * Conventions
+ *   - All pointers named *_host are host memory, all others are device memory
+ *     on the plan's device.  The caller owns every buffer; the plan owns only
+ *     its private descriptor copies and work list.
+ *   - bf16 tensors are raw 16-bit patterns.  q/out: [T, Hq, D]; k_new/v_new:
+ *     [T, Hkv, D]; T = cu_q[batch]; token t of request i, chunk index j is
+ *     t = cu_q[i] + j.  Query head h reads kv head h / (Hq/Hkv).
+ *   - Paged pool: the tile of (page, kv head) starts at element
+ *     page*stride_page + head*stride_head and holds P*D elements in the
+ *     "grouped-K / slot-contiguous-V" layout
+ *         K[slot][d] at ((d/8)*P + slot)*8 + d%8
+ *         V[slot][d] at d*P + slot
+ *     (8-element = 16-byte groups of the head dim: one 16x16x32 MFMA operand
+ *     register set per lane; a wave-wide load of a page tile is contiguous).
+ *     Logical slot n of request i lives in page block_table[i][n / P], in-page
+ *     slot n % P.  Slots at or beyond L_i + c_i and unreferenced pages are
+ *     never read into a result, whatever they hold (NaN included).
+ *   - Every call returns an optimus_status_t (0 = OK, negative = error) and
+ *     never throws.  Kernel launches are asynchronous on the given stream.
+ */
+#ifndef OPTIMUS_ATTN_H_
+#define OPTIMUS_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OPTIMUS_OK = 0,
+  OPTIMUS_ERR_INVALID_ARGUMENT = -1,   /* null pointer, negative size, bad enum       */
+  OPTIMUS_ERR_UNSUPPORTED_SHAPE = -2,  /* head_dim, page_size, Hq % Hkv, layout        */
+  OPTIMUS_ERR_BAD_CU_Q = -3,           /* cu_q[0] != 0 or decreasing                   */
+  OPTIMUS_ERR_BAD_PREFIX = -4,         /* L_i < 0, s_i < 0 or s_i > L_i                */
+  OPTIMUS_ERR_CHUNK_EXCEEDS_BLOCK = -5,/* in-block mode: (L_i - s_i) + c_i > B         */
+  OPTIMUS_ERR_BLOCK_TABLE_TOO_SHORT = -6, /* ceil((L_i+c_i)/P) > max_pages_per_req     */
+  OPTIMUS_ERR_PAGE_OUT_OF_RANGE = -7,  /* a referenced block-table entry not in [0,num_pages) */
+  OPTIMUS_ERR_WORKSPACE_TOO_SMALL = -8,
+  OPTIMUS_ERR_NOT_PLANNED = -9,        /* forward/append before a successful plan_update */
+  OPTIMUS_ERR_NO_DEVICE = -10,         /* device call on a host-only plan              */
+  OPTIMUS_ERR_HIP = -11                /* a HIP runtime call failed; see optimus_last_hip_error */
+} optimus_status_t;
+
+typedef struct optimus_attn_plan optimus_attn_plan_t; /* opaque */
+
+/* Problem geometry, fixed for the life of a plan. */
+typedef struct {
+  int32_t num_q_heads;       /* Hq                                              */
+  int32_t num_kv_heads;      /* Hkv, Hq % Hkv == 0                              */
+  int32_t head_dim;          /* D in {64, 128}                                  */
+  int32_t page_size;         /* P in {16, 32, 64, 128}                          */
+  int32_t block_size;        /* B, diffusion block (32 in the paper's models)   */
+  int32_t mask_mode;         /* 0 in-block streaming (Sec. 7.2 default): chunk
+                                bidirectional.  1 out-block streaming read as
+                                block-causal inside the chunk: chunk key k is
+                                visible to chunk query j iff
+                                (d_i+k)/B <= (d_i+j)/B, d_i = L_i - s_i.        */
+  int32_t out_dtype;         /* 0 bf16, 1 fp32                                  */
+  int32_t kv_layout;         /* must be 1 (layout described above)              */
+  float   softmax_scale;     /* <= 0 -> 1/sqrt(D)                               */
+  int32_t num_pages;         /* pool size, for block-table validation           */
+  int32_t max_pages_per_req; /* row stride of the block table                   */
+  int32_t reserved0;
+  int64_t k_stride_page, k_stride_head; /* elements; multiples of 8             */
+  int64_t v_stride_page, v_stride_head; /* elements; multiples of 8             */
+} optimus_attn_params_t;
+
+/* One unit of device work, exposed so that host tests can check that the plan
+ * covers every (request, kv head, query row, key) exactly once.  The rows of
+ * a (request, kv head) pair are r = j*G + u for chunk token j and head u of
+ * the group (G = Hq/Hkv), r in [0, c_i*G).                                    */
+typedef struct {
+  int32_t req;         /* request index i                                       */
+  int32_t kv_head;     /* g                                                     */
+  int32_t row_begin;   /* first row of this q tile                              */
+  int32_t row_count;   /* rows in this q tile (1..64)                           */
+  int32_t kv_begin;    /* first logical key slot, multiple of 32                */
+  int32_t kv_end;      /* one past the last key slot, <= L_i + c_i              */
+  int32_t part_row;    /* -1: writes final output; else first row of its partial
+                          in the workspace                                      */
+  int32_t q_token0;    /* cu_q[i]                                               */
+} optimus_work_item_t;
+
+/* Create a plan.  device >= 0: HIP device ordinal that all later device calls
+ * of this plan use.  device == -1: host-only plan (validation and planning
+ * work; kv_append / forward return OPTIMUS_ERR_NO_DEVICE).                     */
+int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
+                             optimus_attn_plan_t** plan_out);
+
+/* Per-iteration planning (host).  Validates the descriptors, tiles the query
+ * rows, chooses the KV split of every (request, kv head) so the launch fills
+ * the chip, builds the work list and uploads it.  Arrays are host memory and
+ * are copied; they may be freed on return.
+ *   cu_q_host        [batch+1], cu_q[0] == 0, non-decreasing (c_i = 0 allowed)
+ *   prefix_len_host  [batch]   L_i >= 0 cached tokens
+ *   block_start_host [batch]   s_i, 0 <= s_i <= L_i, origin of the current block
+ *   block_table_host [batch, max_pages_per_req] or NULL (skips page-id checks)
+ *   workspace_bytes_out  bytes of scratch that optimus_attn_forward needs
+ * Must not be called while a forward of the same plan from TWO updates ago is
+ * still running (the device work list is double-buffered).  batch == 0 is a
+ * valid no-op plan.                                                            */
+int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch,
+                             const int32_t* cu_q_host, const int32_t* prefix_len_host,
+                             const int32_t* block_start_host,
+                             const int32_t* block_table_host,
+                             size_t* workspace_bytes_out);
+
+/* Sec. 6: map the chunk's K/V into the paged cache.  Chunk token j of request
+ * i is written to logical slot L_i + j, overwriting the slot (chunk KV is
+ * provisional until commit, Sec. 4.1).  k_new, v_new: bf16 [T, Hkv, D].
+ * Index arithmetic is exact; the payload is a bit copy.                        */
+int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool,
+                      const void* k_new, const void* v_new,
+                      const int32_t* block_table, void* hip_stream);
+
+/* Sec. 6: attention of every chunk over its cached prefix and itself.  The
+ * chunk's K/V must already be in the pool (optimus_kv_append on the same
+ * stream).  out: [T, Hq, D] in params.out_dtype.  workspace: device scratch
+ * of at least the size plan_update reported (may be NULL if that was 0); it
+ * holds split-KV partials and is fully overwritten before it is read.          */
+int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                         const void* v_pool, const int32_t* block_table, void* out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+void optimus_attn_plan_destroy(optimus_attn_plan_t* plan);
+
+/* Introspection of the current work list (host). */
+int32_t optimus_attn_plan_num_work_items(const optimus_attn_plan_t* plan);
+int32_t optimus_attn_plan_num_merge_items(const optimus_attn_plan_t* plan);
+/* Copies up to capacity items; returns the number copied or a negative status. */
+int32_t optimus_attn_plan_get_work_items(const optimus_attn_plan_t* plan,
+                                         optimus_work_item_t* items_out, int32_t capacity);
+
+/* Planner knobs (host).  target_items: aim for at least this many work items
+ * (0 = default: a multiple of the device's compute-unit count).
+ * min_split_tokens / max_split_tokens: bounds on the keys one work item scans
+ * (multiples of 32; 0 = default).                                               */
+int optimus_attn_plan_set_tuning(optimus_attn_plan_t* plan, int32_t target_items,
+                                 int32_t min_split_tokens, int32_t max_split_tokens);
+
+/* Optional timing of the attention main kernel with HIP events recorded on the
+ * caller's stream around its launch.  enable != 0 turns recording on for later
+ * forwards; optimus_attn_last_kernel_ms synchronises on the last end event and
+ * returns the elapsed milliseconds (negative status if none was recorded).     */
+int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable);
+int optimus_attn_last_kernel_ms(optimus_attn_plan_t* plan, float* ms_out);
+
+const char* optimus_status_string(int status);
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char* optimus_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTIMUS_ATTN_H_ */

@@ -1,0 +1,243 @@
+"""ctypes binding of ``liboptimus_attn.so``: argument marshalling only.
+
+Every step of the path (planning, KV append, attention, merge) runs inside the
+C-ABI library; this module converts numpy descriptors and torch device tensors
+to pointers and checks status codes.  There is no fallback: if the library is
+missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboptimus_attn.so")
+_lib = None
+
+EXPORTS = (
+    "optimus_attn_plan_create", "optimus_attn_plan_update", "optimus_kv_append",
+    "optimus_attn_forward", "optimus_attn_plan_destroy", "optimus_attn_plan_num_work_items",
+    "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
+    "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_last_kernel_ms",
+    "optimus_status_string", "optimus_last_hip_error",
+)
+
+
+class OptimusError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = f"{where}: {status_string(status)} ({status})"
+        if status == -11:
+            msg += f": {load_library().optimus_last_hip_error().decode()}"
+        super().__init__(msg)
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [
+        ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("block_size", ctypes.c_int32), ("mask_mode", ctypes.c_int32),
+        ("out_dtype", ctypes.c_int32), ("kv_layout", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("num_pages", ctypes.c_int32),
+        ("max_pages_per_req", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("k_stride_page", ctypes.c_int64), ("k_stride_head", ctypes.c_int64),
+        ("v_stride_page", ctypes.c_int64), ("v_stride_head", ctypes.c_int64),
+    ]
+
+
+class WorkItem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("req", "kv_head", "row_begin", "row_count", "kv_begin", "kv_end", "part_row",
+                 "q_token0")]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2605_24832_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
+        lib.optimus_attn_plan_create.argtypes = [ctypes.POINTER(_CParams), ctypes.c_int,
+                                                 ctypes.POINTER(vp)]
+        lib.optimus_attn_plan_update.argtypes = [vp, i32, i32p, i32p, i32p, i32p,
+                                                 ctypes.POINTER(ctypes.c_size_t)]
+        lib.optimus_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        lib.optimus_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.optimus_attn_plan_destroy.argtypes = [vp]
+        lib.optimus_attn_plan_destroy.restype = None
+        lib.optimus_attn_plan_num_work_items.argtypes = [vp]
+        lib.optimus_attn_plan_num_work_items.restype = i32
+        lib.optimus_attn_plan_num_merge_items.argtypes = [vp]
+        lib.optimus_attn_plan_num_merge_items.restype = i32
+        lib.optimus_attn_plan_get_work_items.argtypes = [vp, ctypes.POINTER(WorkItem), i32]
+        lib.optimus_attn_plan_get_work_items.restype = i32
+        lib.optimus_attn_plan_set_tuning.argtypes = [vp, i32, i32, i32]
+        lib.optimus_attn_set_timing.argtypes = [vp, i32]
+        lib.optimus_attn_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        lib.optimus_status_string.argtypes = [ctypes.c_int]
+        lib.optimus_status_string.restype = ctypes.c_char_p
+        lib.optimus_last_hip_error.argtypes = []
+        lib.optimus_last_hip_error.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().optimus_status_string(int(status)).decode()
+
+
+@dataclass
+class AttnParams:
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    page_size: int
+    block_size: int
+    num_pages: int
+    max_pages_per_req: int
+    mask_mode: int = 0
+    out_dtype: int = 0          # 0 bf16, 1 fp32
+    kv_layout: int = 1
+    softmax_scale: float = 0.0  # <= 0 -> 1/sqrt(D)
+    k_stride_page: int | None = None
+    k_stride_head: int | None = None
+    v_stride_page: int | None = None
+    v_stride_head: int | None = None
+
+    def to_c(self) -> _CParams:
+        tile = self.page_size * self.head_dim
+        c = _CParams()
+        for f in ("num_q_heads", "num_kv_heads", "head_dim", "page_size", "block_size",
+                  "mask_mode", "out_dtype", "kv_layout", "num_pages", "max_pages_per_req"):
+            setattr(c, f, int(getattr(self, f)))
+        c.softmax_scale = float(self.softmax_scale)
+        c.k_stride_head = tile if self.k_stride_head is None else self.k_stride_head
+        c.v_stride_head = tile if self.v_stride_head is None else self.v_stride_head
+        c.k_stride_page = self.num_kv_heads * tile if self.k_stride_page is None else self.k_stride_page
+        c.v_stride_page = self.num_kv_heads * tile if self.v_stride_page is None else self.v_stride_page
+        return c
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _stream_ptr(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+class Plan:
+    """Owner of one ``optimus_attn_plan_t``; method names follow the C entry points."""
+
+    def __init__(self, params: AttnParams, device: int = 0):
+        self._lib = load_library()
+        self.params = params
+        self.device = device
+        self._h = ctypes.c_void_p(0)
+        cp = params.to_c()
+        rc = self._lib.optimus_attn_plan_create(ctypes.byref(cp), int(device), ctypes.byref(self._h))
+        if rc != 0:
+            self._h = ctypes.c_void_p(0)
+            raise OptimusError(rc, "optimus_attn_plan_create")
+        self.workspace_bytes = 0
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.optimus_attn_plan_destroy(self._h)
+            self._h = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def plan_update(self, cu_q, prefix_len, block_start, block_table=None) -> int:
+        cu, cu_p = _i32(cu_q)
+        pl, pl_p = _i32(prefix_len)
+        bs, bs_p = _i32(block_start)
+        if block_table is None:
+            bt_p = ctypes.POINTER(ctypes.c_int32)()
+        else:
+            bt, bt_p = _i32(block_table)
+        if len(cu) != len(pl) + 1 or len(bs) != len(pl):
+            raise ValueError("cu_q must have batch+1 entries, prefix_len and block_start batch")
+        ws = ctypes.c_size_t(0)
+        rc = self._lib.optimus_attn_plan_update(self._h, len(pl), cu_p, pl_p, bs_p, bt_p,
+                                                ctypes.byref(ws))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_plan_update")
+        self.workspace_bytes = int(ws.value)
+        return self.workspace_bytes
+
+    def set_tuning(self, target_items=0, min_split_tokens=0, max_split_tokens=0):
+        rc = self._lib.optimus_attn_plan_set_tuning(self._h, target_items, min_split_tokens,
+                                                    max_split_tokens)
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_plan_set_tuning")
+
+    def num_work_items(self) -> int:
+        return int(self._lib.optimus_attn_plan_num_work_items(self._h))
+
+    def num_merge_items(self) -> int:
+        return int(self._lib.optimus_attn_plan_num_merge_items(self._h))
+
+    def work_items(self) -> np.ndarray:
+        """Structured array with the fields of ``optimus_work_item_t``."""
+        n = self.num_work_items()
+        buf = (WorkItem * max(n, 1))()
+        got = self._lib.optimus_attn_plan_get_work_items(self._h, buf, n)
+        if got < 0:
+            raise OptimusError(got, "optimus_attn_plan_get_work_items")
+        arr = np.frombuffer(buf, dtype=np.dtype([(f, np.int32) for f, _ in WorkItem._fields_]))
+        return arr[:got].copy()
+
+    def kv_append(self, k_pool, v_pool, k_new, v_new, block_table, stream=None) -> None:
+        rc = self._lib.optimus_kv_append(self._h, _ptr(k_pool), _ptr(v_pool), _ptr(k_new),
+                                         _ptr(v_new), _ptr(block_table), _stream_ptr(stream))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_kv_append")
+
+    def attn_forward(self, q, k_pool, v_pool, block_table, out, workspace=None, stream=None) -> None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        rc = self._lib.optimus_attn_forward(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                            _ptr(block_table), _ptr(out), _ptr(workspace),
+                                            ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_forward")
+
+    def set_timing(self, enable: bool) -> None:
+        rc = self._lib.optimus_attn_set_timing(self._h, 1 if enable else 0)
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_set_timing")
+
+    def last_kernel_ms(self) -> float:
+        ms = ctypes.c_float(0)
+        rc = self._lib.optimus_attn_last_kernel_ms(self._h, ctypes.byref(ms))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_last_kernel_ms")
+        return float(ms.value)
