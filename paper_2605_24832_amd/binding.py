@@ -144,8 +144,11 @@ def _i32(a):
 
 
 def _stream_ptr(stream) -> ctypes.c_void_p:
+    """torch stream -> hipStream_t; None = torch's current stream (the null stream without a GPU)."""
     if stream is None:
         import torch
+        if not torch.cuda.is_available():
+            return ctypes.c_void_p(0)
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream)
 

@@ -1,0 +1,311 @@
+// C ABI of the chunked block-diffusion attention library: plan objects, device
+// upload of the per-iteration work list, and the enqueue of the kernels.
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "plan_internal.h"
+
+namespace optimus {
+
+static thread_local std::string g_hip_error;
+
+void set_hip_error(int hip_err, const char* where) {
+  g_hip_error = std::string(where) + ": " + hipGetErrorString((hipError_t)hip_err);
+}
+
+#define OPT_HIP(call, where)                          \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) {                           \
+      optimus::set_hip_error((int)e_, where);         \
+      return OPTIMUS_ERR_HIP;                         \
+    }                                                 \
+  } while (0)
+
+}  // namespace optimus
+
+using namespace optimus;
+
+struct optimus_attn_plan {
+  optimus_attn_params_t params{};
+  int device = -1;
+  int num_cus = 256;
+  Tuning tuning;
+  HostPlan host;
+  bool planned = false;
+
+  // device copies of the descriptors and the work list, double-buffered
+  int32_t* dev_buf[2] = {nullptr, nullptr};
+  size_t dev_cap[2] = {0, 0};   // in int32
+  int cur = 0;
+  int32_t* pinned = nullptr;
+  size_t pinned_cap = 0;
+  hipStream_t copy_stream = nullptr;
+  // offsets (int32 units) into dev_buf[cur]
+  size_t off_items = 0, off_merges = 0, off_token_req = 0, off_cu_q = 0, off_prefix = 0, off_bstart = 0;
+
+  bool timing = false;
+  bool timed = false;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+};
+
+static int use_device(const optimus_attn_plan* plan) {
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  OPT_HIP(hipSetDevice(plan->device), "hipSetDevice");
+  return OPTIMUS_OK;
+}
+
+extern "C" {
+
+int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
+                             optimus_attn_plan_t** plan_out) {
+  if (!params || !plan_out || device < -1) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  *plan_out = nullptr;
+  int rc = validate_params(*params);
+  if (rc != OPTIMUS_OK) return rc;
+  optimus_attn_plan* plan = new (std::nothrow) optimus_attn_plan();
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  plan->params = *params;
+  plan->device = device;
+  if (device >= 0) {
+    hipError_t e = hipSetDevice(device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&plan->copy_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+      set_hip_error((int)e, "plan_create");
+      delete plan;
+      return OPTIMUS_ERR_HIP;
+    }
+    plan->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  *plan_out = plan;
+  return OPTIMUS_OK;
+}
+
+int optimus_attn_plan_set_tuning(optimus_attn_plan_t* plan, int32_t target_items,
+                                 int32_t min_split_tokens, int32_t max_split_tokens) {
+  if (!plan || target_items < 0 || min_split_tokens < 0 || max_split_tokens < 0)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (min_split_tokens % kTileTokens != 0 || max_split_tokens % kTileTokens != 0)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  plan->tuning.target_items = target_items;
+  plan->tuning.min_split_tokens = min_split_tokens;
+  plan->tuning.max_split_tokens = max_split_tokens;
+  return OPTIMUS_OK;
+}
+
+int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int32_t* cu_q_host,
+                             const int32_t* prefix_len_host, const int32_t* block_start_host,
+                             const int32_t* block_table_host, size_t* workspace_bytes_out) {
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  plan->planned = false;
+  int rc = build_host_plan(plan->params, plan->tuning, plan->num_cus, batch, cu_q_host,
+                           prefix_len_host, block_start_host, block_table_host, &plan->host);
+  if (rc != OPTIMUS_OK) return rc;
+  if (workspace_bytes_out) *workspace_bytes_out = plan->host.workspace_bytes;
+  if (plan->device < 0 || batch == 0) {
+    plan->planned = true;
+    return OPTIMUS_OK;
+  }
+  rc = use_device(plan);
+  if (rc != OPTIMUS_OK) return rc;
+
+  const HostPlan& hp = plan->host;
+  static_assert(sizeof(optimus_work_item_t) == 32 && sizeof(MergeItem) == 32, "8 x int32 records");
+  size_t off = 0;
+  auto take = [&](size_t n_i32) { size_t o = off; off += (n_i32 + 3) & ~size_t(3); return o; };
+  plan->off_items = take(hp.items.size() * 8);
+  plan->off_merges = take(hp.merges.size() * 8);
+  plan->off_token_req = take(hp.token_req.size());
+  plan->off_cu_q = take(hp.cu_q.size());
+  plan->off_prefix = take(hp.prefix_len.size());
+  plan->off_bstart = take(hp.block_start.size());
+  const size_t total = off;
+
+  if (plan->pinned_cap < total) {
+    if (plan->pinned) OPT_HIP(hipHostFree(plan->pinned), "hipHostFree");
+    plan->pinned = nullptr;
+    plan->pinned_cap = 0;
+    const size_t cap = total + total / 2 + 1024;
+    OPT_HIP(hipHostMalloc((void**)&plan->pinned, cap * sizeof(int32_t), hipHostMallocDefault),
+            "hipHostMalloc");
+    plan->pinned_cap = cap;
+  }
+  const int nb = plan->cur ^ 1;
+  if (plan->dev_cap[nb] < total) {
+    if (plan->dev_buf[nb]) OPT_HIP(hipFree(plan->dev_buf[nb]), "hipFree");
+    plan->dev_buf[nb] = nullptr;
+    plan->dev_cap[nb] = 0;
+    const size_t cap = total + total / 2 + 1024;
+    OPT_HIP(hipMalloc((void**)&plan->dev_buf[nb], cap * sizeof(int32_t)), "hipMalloc");
+    plan->dev_cap[nb] = cap;
+  }
+  int32_t* h = plan->pinned;
+  if (!hp.items.empty()) std::memcpy(h + plan->off_items, hp.items.data(), hp.items.size() * 32);
+  if (!hp.merges.empty()) std::memcpy(h + plan->off_merges, hp.merges.data(), hp.merges.size() * 32);
+  if (!hp.token_req.empty())
+    std::memcpy(h + plan->off_token_req, hp.token_req.data(), hp.token_req.size() * 4);
+  std::memcpy(h + plan->off_cu_q, hp.cu_q.data(), hp.cu_q.size() * 4);
+  std::memcpy(h + plan->off_prefix, hp.prefix_len.data(), hp.prefix_len.size() * 4);
+  std::memcpy(h + plan->off_bstart, hp.block_start.data(), hp.block_start.size() * 4);
+  OPT_HIP(hipMemcpyAsync(plan->dev_buf[nb], h, total * sizeof(int32_t), hipMemcpyHostToDevice,
+                         plan->copy_stream),
+          "hipMemcpyAsync(work list)");
+  OPT_HIP(hipStreamSynchronize(plan->copy_stream), "hipStreamSynchronize(work list)");
+  plan->cur = nb;
+  plan->planned = true;
+  return OPTIMUS_OK;
+}
+
+int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, const void* k_new,
+                      const void* v_new, const int32_t* block_table, void* hip_stream) {
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (!plan->planned) return OPTIMUS_ERR_NOT_PLANNED;
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  if (plan->host.total_q == 0) return OPTIMUS_OK;
+  if (!k_pool || !v_pool || !k_new || !v_new || !block_table) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)k_new | (uintptr_t)v_new) & 15)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  int rc = use_device(plan);
+  if (rc != OPTIMUS_OK) return rc;
+  const int32_t* d = plan->dev_buf[plan->cur];
+  return launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
+                          (const uint16_t*)v_new, block_table, d + plan->off_token_req,
+                          d + plan->off_cu_q, d + plan->off_prefix, plan->host.total_q, hip_stream);
+}
+
+int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                         const void* v_pool, const int32_t* block_table, void* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (!plan->planned) return OPTIMUS_ERR_NOT_PLANNED;
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  const HostPlan& hp = plan->host;
+  if (hp.items.empty()) return OPTIMUS_OK;
+  if (!q || !k_pool || !v_pool || !block_table || !out) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out | (uintptr_t)workspace) & 15)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (hp.workspace_bytes > 0 && (!workspace || workspace_bytes < hp.workspace_bytes))
+    return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
+  int rc = use_device(plan);
+  if (rc != OPTIMUS_OK) return rc;
+
+  const optimus_attn_params_t& p = plan->params;
+  const int32_t* d = plan->dev_buf[plan->cur];
+  KernelArgs a{};
+  a.q = (const uint16_t*)q;
+  a.k_pool = (const uint16_t*)k_pool;
+  a.v_pool = (const uint16_t*)v_pool;
+  a.block_table = block_table;
+  a.items = reinterpret_cast<const optimus_work_item_t*>(d + plan->off_items);
+  a.merges = reinterpret_cast<const MergeItem*>(d + plan->off_merges);
+  a.prefix_len = d + plan->off_prefix;
+  a.block_start = d + plan->off_bstart;
+  a.out = out;
+  a.ws_o = reinterpret_cast<float*>(workspace);
+  a.ws_ml = a.ws_o ? a.ws_o + (size_t)hp.part_rows * p.head_dim : nullptr;
+  a.k_stride_page = p.k_stride_page; a.k_stride_head = p.k_stride_head;
+  a.v_stride_page = p.v_stride_page; a.v_stride_head = p.v_stride_head;
+  a.num_q_heads = p.num_q_heads;
+  a.group = p.num_q_heads / p.num_kv_heads;
+  a.max_pages_per_req = p.max_pages_per_req;
+  a.out_fp32 = p.out_dtype == 1;
+  a.mask_mode = p.mask_mode;
+  a.block_size = p.block_size;
+  const float scale = p.softmax_scale > 0.f ? p.softmax_scale : 1.0f / std::sqrt((float)p.head_dim);
+  a.scale_log2 = scale * 1.4426950408889634f;
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  if (plan->timing) {
+    if (!plan->ev0) {
+      OPT_HIP(hipEventCreate(&plan->ev0), "hipEventCreate");
+      OPT_HIP(hipEventCreate(&plan->ev1), "hipEventCreate");
+    }
+    OPT_HIP(hipEventRecord(plan->ev0, s), "hipEventRecord");
+  }
+  for (int nt = 1; nt <= kMaxSubtiles; ++nt) {
+    const int32_t first = hp.class_begin[nt - 1], n = hp.class_begin[nt] - first;
+    rc = launch_attention(p, a, nt, first, n, hip_stream);
+    if (rc != OPTIMUS_OK) return rc;
+  }
+  if (plan->timing) {
+    OPT_HIP(hipEventRecord(plan->ev1, s), "hipEventRecord");
+    plan->timed = true;
+  }
+  return launch_merge(p, a, (int32_t)hp.merges.size(), hip_stream);
+}
+
+void optimus_attn_plan_destroy(optimus_attn_plan_t* plan) {
+  if (!plan) return;
+  if (plan->device >= 0 && hipSetDevice(plan->device) == hipSuccess) {
+    for (int b = 0; b < 2; ++b)
+      if (plan->dev_buf[b]) (void)hipFree(plan->dev_buf[b]);
+    if (plan->pinned) (void)hipHostFree(plan->pinned);
+    if (plan->copy_stream) (void)hipStreamDestroy(plan->copy_stream);
+    if (plan->ev0) (void)hipEventDestroy(plan->ev0);
+    if (plan->ev1) (void)hipEventDestroy(plan->ev1);
+  }
+  delete plan;
+}
+
+int32_t optimus_attn_plan_num_work_items(const optimus_attn_plan_t* plan) {
+  return plan ? (int32_t)plan->host.items.size() : OPTIMUS_ERR_INVALID_ARGUMENT;
+}
+
+int32_t optimus_attn_plan_num_merge_items(const optimus_attn_plan_t* plan) {
+  return plan ? (int32_t)plan->host.merges.size() : OPTIMUS_ERR_INVALID_ARGUMENT;
+}
+
+int32_t optimus_attn_plan_get_work_items(const optimus_attn_plan_t* plan,
+                                         optimus_work_item_t* items_out, int32_t capacity) {
+  if (!plan || capacity < 0 || (capacity > 0 && !items_out)) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  const int32_t n = std::min<int32_t>(capacity, (int32_t)plan->host.items.size());
+  if (n > 0) std::memcpy(items_out, plan->host.items.data(), (size_t)n * sizeof(optimus_work_item_t));
+  return n;
+}
+
+int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable) {
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  plan->timing = enable != 0;
+  if (!plan->timing) plan->timed = false;
+  return OPTIMUS_OK;
+}
+
+int optimus_attn_last_kernel_ms(optimus_attn_plan_t* plan, float* ms_out) {
+  if (!plan || !ms_out) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  if (!plan->timed) return OPTIMUS_ERR_NOT_PLANNED;
+  int rc = use_device(plan);
+  if (rc != OPTIMUS_OK) return rc;
+  OPT_HIP(hipEventSynchronize(plan->ev1), "hipEventSynchronize");
+  OPT_HIP(hipEventElapsedTime(ms_out, plan->ev0, plan->ev1), "hipEventElapsedTime");
+  return OPTIMUS_OK;
+}
+
+const char* optimus_status_string(int status) {
+  switch (status) {
+    case OPTIMUS_OK: return "ok";
+    case OPTIMUS_ERR_INVALID_ARGUMENT: return "invalid argument";
+    case OPTIMUS_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case OPTIMUS_ERR_BAD_CU_Q: return "cu_q must start at 0 and be non-decreasing";
+    case OPTIMUS_ERR_BAD_PREFIX: return "prefix length / block start out of range";
+    case OPTIMUS_ERR_CHUNK_EXCEEDS_BLOCK: return "chunk leaves the current block in in-block mode";
+    case OPTIMUS_ERR_BLOCK_TABLE_TOO_SHORT: return "block table row too short for prefix + chunk";
+    case OPTIMUS_ERR_PAGE_OUT_OF_RANGE: return "block table entry outside the pool";
+    case OPTIMUS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case OPTIMUS_ERR_NOT_PLANNED: return "no successful plan_update (or nothing recorded) yet";
+    case OPTIMUS_ERR_NO_DEVICE: return "host-only plan has no device";
+    case OPTIMUS_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* optimus_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,518 @@
+// gfx950 (CDNA4) kernels of the chunked block-diffusion attention step
+// (Optimus Sec. 6: paged attention over variable-length query chunks, plus
+// the mapping of per-chunk KV into the paged cache).
+//
+// attention main kernel ("split-wave"):
+//   One workgroup of 4 wave64 per work item = (request, kv head, <=64 query
+//   rows, key range).  The rows of a (request, kv head) pair are all G query
+//   heads of the group x the chunk tokens, so K/V are fetched once per group.
+//   The 4 waves take the 32-key tiles of the range round-robin; each wave keeps
+//   its own online-softmax state and the waves are merged through LDS at the
+//   end.  K and V go from HBM straight into MFMA operand registers: the pool
+//   layout (K in 16-byte d-groups, slot-major; V slot-contiguous) makes every
+//   wave-wide load a contiguous run, and the transposed formulation
+//       S^T = K Q^T   (v_mfma_f32_16x16x32_bf16, A = K tile, B = Q^T)
+//       O^T = V^T P^T (A = V^T tile, B = P^T)
+//   leaves the S^T accumulator of a lane exactly in the B-operand layout the
+//   second product needs, so P never moves between lanes; only the row max
+//   crosses lanes (two xor shuffles over the 4 lane groups).
+//
+// 16x16x32 bf16 MFMA register layout (lane = 16*kg + r, kg 0..3, r 0..15):
+//   A: row r,  k = 8*kg .. 8*kg+7      B: col r, k = 8*kg .. 8*kg+7
+//   C/D: 4 floats, rows 4*kg .. 4*kg+3, col r
+#include <hip/hip_runtime.h>
+
+#include "plan_internal.h"
+
+namespace optimus {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int W = kWavesPerBlock;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float xor_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+__device__ __forceinline__ float xor_sum(float v) {
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+template <int D>
+struct KvTile {
+  bf16x8 k[2][D / 32];   // [16-key half][d step of 32]
+  u32x2 v[D / 16][2];    // [16-wide d block][16-key half] : 4 keys x bf16
+};
+
+// Issue the loads of one 32-key tile.  `bt` is the request's block-table row,
+// `last_page` the index of the last page that holds a key of this request.
+template <int D, int LGP>
+__device__ __forceinline__ void load_tile(KvTile<D>& t, int tile, const int32_t* __restrict__ bt,
+                                          int last_page, const char* __restrict__ kbase,
+                                          const char* __restrict__ vbase, int64_t k_stride_page_b,
+                                          int64_t v_stride_page_b, int r16, int kg) {
+  constexpr int P = 1 << LGP;
+  constexpr int KS = D / 32, DB = D / 16;
+  if constexpr (LGP == 4) {
+    // two pages per tile; the second may lie beyond the request's last page
+    // (then its keys are all masked): clamp so the load stays in a valid page.
+    const int pi0 = tile * 2;
+    const int pi1 = min(pi0 + 1, last_page);
+    const int64_t pg0 = bt[pi0], pg1 = bt[pi1];
+    const char* k0 = kbase + pg0 * k_stride_page_b;
+    const char* k1 = kbase + pg1 * k_stride_page_b;
+    const char* v0 = vbase + pg0 * v_stride_page_b;
+    const char* v1 = vbase + pg1 * v_stride_page_b;
+    const uint32_t koff = (uint32_t)(kg * P + r16) * 16u;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      t.k[0][s] = *reinterpret_cast<const bf16x8*>(k0 + koff + s * (4 * P * 16));
+      t.k[1][s] = *reinterpret_cast<const bf16x8*>(k1 + koff + s * (4 * P * 16));
+    }
+    const uint32_t voff = (uint32_t)(r16 * P + 4 * kg) * 2u;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      t.v[db][0] = *reinterpret_cast<const u32x2*>(v0 + voff + db * (16 * P * 2));
+      t.v[db][1] = *reinterpret_cast<const u32x2*>(v1 + voff + db * (16 * P * 2));
+    }
+  } else {
+    const int pi = (tile * kTileTokens) >> LGP;
+    const int slot0 = (tile * kTileTokens) & (P - 1);
+    const int64_t pg = bt[pi];
+    const char* k0 = kbase + pg * k_stride_page_b;
+    const char* v0 = vbase + pg * v_stride_page_b;
+    const uint32_t koff = (uint32_t)(kg * P + slot0 + r16) * 16u;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      t.k[0][s] = *reinterpret_cast<const bf16x8*>(k0 + koff + s * (4 * P * 16));
+      t.k[1][s] = *reinterpret_cast<const bf16x8*>(k0 + koff + s * (4 * P * 16) + 16 * 16);
+    }
+    const uint32_t voff = (uint32_t)(r16 * P + slot0 + 4 * kg) * 2u;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      t.v[db][0] = *reinterpret_cast<const u32x2*>(v0 + voff + db * (16 * P * 2));
+      t.v[db][1] = *reinterpret_cast<const u32x2*>(v0 + voff + db * (16 * P * 2) + 16 * 2);
+    }
+  }
+}
+
+template <int D, int NT>
+struct SoftmaxState {
+  float m[NT];            // running max (log2 units), replicated over the 4 lane groups
+  float l[NT];            // this lane's share of the running sum
+  f32x4 acc[NT][D / 16];  // O^T: rows d = 16*db + 4*kg + j, col = query row r16
+};
+
+// One 32-key tile against NT x 16 query rows.
+//   key_base: logical slot of the tile's first key
+//   kv_end:   keys at or beyond are outside the item (only the tail tile)
+//   vis_end:  per lane / subtile, first key the lane's query row may not see
+template <int D, int NT>
+__device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, KvTile<D>& t,
+                                             const bf16x8 (&qreg)[NT][D / 32], int key_base,
+                                             int kv_end, const int (&vis_end)[NT], bool masked,
+                                             float sc, int kg) {
+  constexpr int KS = D / 32, DB = D / 16;
+  if (masked) {
+    // zero V of keys outside the item so that 0 * garbage cannot become NaN
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int cnt = kv_end - (key_base + 16 * hf + 4 * kg);  // valid keys among this lane's 4
+      const uint32_t m0 = cnt >= 2 ? 0xffffffffu : (cnt == 1 ? 0x0000ffffu : 0u);
+      const uint32_t m1 = cnt >= 4 ? 0xffffffffu : (cnt == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        t.v[db][hf].x &= m0;
+        t.v[db][hf].y &= m1;
+      }
+    }
+  }
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][s], qreg[nt][s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][s], qreg[nt][s], s1, 0, 0, 0);
+    }
+    if (masked) {
+      const int lim = min(kv_end, vis_end[nt]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int n = key_base + 4 * kg + j;
+        s0[j] = n < lim ? s0[j] : -INFINITY;
+        s1[j] = n + 16 < lim ? s1[j] : -INFINITY;
+      }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                     fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+    mx = xor_max(mx);
+    const float m_new = fmaxf(st.m[nt], mx * sc);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // row with no visible key so far
+    const float alpha = fast_exp2(st.m[nt] - m_use);
+    st.m[nt] = m_new;
+    float p[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      p[j] = fast_exp2(fmaf(s0[j], sc, -m_use));
+      p[4 + j] = fast_exp2(fmaf(s1[j], sc, -m_use));
+    }
+    st.l[nt] = fmaf(st.l[nt], alpha, ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])));
+    bf16x8 pt;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pt[j] = (__bf16)p[j];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      f32x4 a = st.acc[nt][db];
+      a *= alpha;
+      u32x4 vv = {t.v[db][0].x, t.v[db][0].y, t.v[db][1].x, t.v[db][1].y};
+      st.acc[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+          __builtin_bit_cast(bf16x8, vv), pt, a, 0, 0, 0);
+    }
+  }
+}
+
+template <int D, int LGP, int NT>
+__global__ __launch_bounds__(W * 64, (NT == 1 ? 2 : 1)) void attn_split_wave_kernel(KernelArgs a, int first_item) {
+  constexpr int KS = D / 32, DB = D / 16;
+  constexpr int OPAD = D + 4;
+  __shared__ float sm_o[W][16][OPAD];
+  __shared__ float sm_m[W][NT * 16];
+  __shared__ float sm_l[W][NT * 16];
+
+  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int G = a.group;
+
+  // ---- Q^T B operands: col r16 = query row, k = d ----
+  bf16x8 qreg[NT][KS];
+  int vis_end[NT];
+  const int L = a.prefix_len[it.req];
+  const int d_in = L - a.block_start[it.req];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int rl = nt * 16 + r16;
+    const bool valid = rl < it.row_count;
+    const int row = it.row_begin + (valid ? rl : 0);
+    const int j = row / G, u = row - j * G;
+    const uint16_t* qp =
+        a.q + ((int64_t)(it.q_token0 + j) * a.num_q_heads + it.kv_head * G + u) * D + kg * 8;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      u32x4 x = *reinterpret_cast<const u32x4*>(qp + s * 32);
+      if (!valid) x = u32x4{0u, 0u, 0u, 0u};
+      qreg[nt][s] = __builtin_bit_cast(bf16x8, x);
+    }
+    // block-causal variant: chunk key k visible iff (d_in+k)/B <= (d_in+j)/B
+    vis_end[nt] = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + j) / a.block_size + 1) * a.block_size - d_in;
+  }
+  // first key any row of the request might not see (uniform)
+  const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
+  const int mask_from = min(it.kv_end, vis_min);
+
+  SoftmaxState<D, NT> st;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    st.m[nt] = -INFINITY;
+    st.l[nt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) st.acc[nt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int32_t* bt = a.block_table + (int64_t)it.req * a.max_pages_per_req;
+  const int last_page = (it.kv_end - 1) >> LGP;
+  const char* kbase = reinterpret_cast<const char*>(a.k_pool + (int64_t)it.kv_head * a.k_stride_head);
+  const char* vbase = reinterpret_cast<const char*>(a.v_pool + (int64_t)it.kv_head * a.v_stride_head);
+  const int64_t kspb = a.k_stride_page * 2, vspb = a.v_stride_page * 2;
+  const float sc = a.scale_log2;
+
+  const int tile_lo = it.kv_begin / kTileTokens;
+  const int tile_hi = (it.kv_end + kTileTokens - 1) / kTileTokens;
+  // this wave's tiles: tile_lo + wave + W*i, i in [0, n)
+  const int n = (tile_hi - tile_lo - wave + W - 1) / W;
+  const int t0 = tile_lo + wave;
+
+  KvTile<D> ta, tb;
+  auto LOAD = [&](KvTile<D>& t, int i) {
+    load_tile<D, LGP>(t, t0 + W * i, bt, last_page, kbase, vbase, kspb, vspb, r16, kg);
+  };
+  auto COMPUTE = [&](KvTile<D>& t, int i) {
+    const int key_base = (t0 + W * i) * kTileTokens;
+    const bool masked = key_base + kTileTokens > mask_from;
+    compute_tile<D, NT>(st, t, qreg, key_base, it.kv_end, vis_end, masked, sc, kg);
+  };
+  if (n > 0) {
+    LOAD(ta, 0);
+    int i = 0;
+    while (i + 2 < n) {
+      LOAD(tb, i + 1);
+      COMPUTE(ta, i);
+      LOAD(ta, i + 2);
+      COMPUTE(tb, i + 1);
+      i += 2;
+    }
+    if (i + 1 < n) {
+      LOAD(tb, i + 1);
+      COMPUTE(ta, i);
+      COMPUTE(tb, i + 1);
+    } else {
+      COMPUTE(ta, i);
+    }
+  }
+
+  // ---- merge the W waves through LDS ----
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const float lsum = xor_sum(st.l[nt]);
+    if (kg == 0) {
+      sm_m[wave][nt * 16 + r16] = st.m[nt];
+      sm_l[wave][nt * 16 + r16] = lsum;
+    }
+  }
+  __syncthreads();
+  float own_scale[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < W; ++w) M = fmaxf(M, sm_m[w][nt * 16 + r16]);
+    const float Mu = M == -INFINITY ? 0.f : M;
+    own_scale[nt] = fast_exp2(st.m[nt] - Mu);
+  }
+  const int tid = threadIdx.x;
+  constexpr int CH = D / 16;              // floats per thread in the reduction (8 or 4)
+  const int orow = tid >> 4, ocol = (tid & 15) * CH;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    if (nt * 16 < it.row_count) {  // uniform
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        f32x4 v = st.acc[nt][db] * own_scale[nt];
+        *reinterpret_cast<f32x4*>(&sm_o[wave][r16][db * 16 + 4 * kg]) = v;
+      }
+    }
+    __syncthreads();
+    const int rl = nt * 16 + orow;
+    if (rl < it.row_count) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < W; ++w) M = fmaxf(M, sm_m[w][rl]);
+      const float Mu = M == -INFINITY ? 0.f : M;
+      float lt = 0.f;
+#pragma unroll
+      for (int w = 0; w < W; ++w) lt += fast_exp2(sm_m[w][rl] - Mu) * sm_l[w][rl];
+      float o[CH];
+#pragma unroll
+      for (int c = 0; c < CH; ++c) o[c] = 0.f;
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+#pragma unroll
+        for (int c = 0; c < CH; c += 4) {
+          f32x4 v = *reinterpret_cast<const f32x4*>(&sm_o[w][orow][ocol + c]);
+          o[c] += v[0]; o[c + 1] += v[1]; o[c + 2] += v[2]; o[c + 3] += v[3];
+        }
+      if (it.part_row >= 0) {
+        float* po = a.ws_o + (int64_t)(it.part_row + rl) * D + ocol;
+#pragma unroll
+        for (int c = 0; c < CH; c += 4)
+          *reinterpret_cast<f32x4*>(po + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
+        if ((tid & 15) == 0) {
+          float* pml = a.ws_ml + (int64_t)(it.part_row + rl) * 2;
+          pml[0] = M;
+          pml[1] = lt;
+        }
+      } else {
+        const float inv = 1.f / lt;
+        const int row = it.row_begin + rl;
+        const int j = row / G, u = row - j * G;
+        const int64_t off = ((int64_t)(it.q_token0 + j) * a.num_q_heads + it.kv_head * G + u) * D + ocol;
+        if (a.out_fp32) {
+          float* po = reinterpret_cast<float*>(a.out) + off;
+#pragma unroll
+          for (int c = 0; c < CH; c += 4)
+            *reinterpret_cast<f32x4*>(po + c) =
+                f32x4{o[c] * inv, o[c + 1] * inv, o[c + 2] * inv, o[c + 3] * inv};
+        } else {
+          __bf16* po = reinterpret_cast<__bf16*>(a.out) + off;
+#pragma unroll
+          for (int c = 0; c < CH; c += 4) {
+            bf16x4 b;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b[e] = (__bf16)(o[c + e] * inv);
+            *reinterpret_cast<bf16x4*>(po + c) = b;
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Merge of split-KV partials: for each row, M = max_s m_s,
+//   o = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
+// Block (256 threads) = (merge item, group of 16 rows); thread = (row, D/16 columns).
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
+  const MergeItem mi = a.merges[blockIdx.x];
+  constexpr int CH = D / 16;
+  const int tid = threadIdx.x;
+  const int rl = blockIdx.y * 16 + (tid >> 4);
+  const int ocol = (tid & 15) * CH;
+  if (rl >= mi.row_count) return;
+  float M = -INFINITY;
+  for (int s = 0; s < mi.n_splits; ++s)
+    M = fmaxf(M, a.ws_ml[(int64_t)(mi.first_part_row + s * mi.row_count + rl) * 2]);
+  const float Mu = M == -INFINITY ? 0.f : M;
+  float lt = 0.f;
+  float o[CH];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) o[c] = 0.f;
+  for (int s = 0; s < mi.n_splits; ++s) {
+    const int64_t pr = mi.first_part_row + s * mi.row_count + rl;
+    const float w = fast_exp2(a.ws_ml[pr * 2] - Mu);
+    lt = fmaf(w, a.ws_ml[pr * 2 + 1], lt);
+    const float* po = a.ws_o + pr * D + ocol;
+#pragma unroll
+    for (int c = 0; c < CH; c += 4) {
+      f32x4 v = *reinterpret_cast<const f32x4*>(po + c);
+      o[c] = fmaf(w, v[0], o[c]); o[c + 1] = fmaf(w, v[1], o[c + 1]);
+      o[c + 2] = fmaf(w, v[2], o[c + 2]); o[c + 3] = fmaf(w, v[3], o[c + 3]);
+    }
+  }
+  const float inv = 1.f / lt;
+  const int G = a.group;
+  const int row = mi.row_begin + rl;
+  const int j = row / G, u = row - j * G;
+  const int64_t off = ((int64_t)(mi.q_token0 + j) * a.num_q_heads + mi.kv_head * G + u) * D + ocol;
+  if (a.out_fp32) {
+    float* po = reinterpret_cast<float*>(a.out) + off;
+#pragma unroll
+    for (int c = 0; c < CH; c += 4)
+      *reinterpret_cast<f32x4*>(po + c) = f32x4{o[c] * inv, o[c + 1] * inv, o[c + 2] * inv, o[c + 3] * inv};
+  } else {
+    __bf16* po = reinterpret_cast<__bf16*>(a.out) + off;
+#pragma unroll
+    for (int c = 0; c < CH; c += 4) {
+      bf16x4 b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) b[e] = (__bf16)(o[c + e] * inv);
+      *reinterpret_cast<bf16x4*>(po + c) = b;
+    }
+  }
+}
+
+// KV append: chunk token j of request i -> logical slot L_i + j of the pool.
+// Block = (token, kv head); threads 0..D/8-1 copy K in 16-byte groups, all D
+// threads copy one V element each (slot-contiguous layout: stride P).
+template <int D>
+__global__ __launch_bounds__(D) void kv_append_kernel(
+    uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const uint16_t* __restrict__ k_new,
+    const uint16_t* __restrict__ v_new, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ token_req, const int32_t* __restrict__ cu_q,
+    const int32_t* __restrict__ prefix_len, int num_kv_heads, int page_size, int lgp,
+    int max_pages_per_req, int64_t k_stride_page, int64_t k_stride_head, int64_t v_stride_page,
+    int64_t v_stride_head) {
+  const int t = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
+  const int i = token_req[t];
+  const int n = prefix_len[i] + (t - cu_q[i]);
+  const int64_t page = block_table[(int64_t)i * max_pages_per_req + (n >> lgp)];
+  const int slot = n & (page_size - 1);
+  const int64_t src = ((int64_t)t * num_kv_heads + g) * D;
+  if (d < D / 8) {
+    const u32x4 x = *reinterpret_cast<const u32x4*>(k_new + src + d * 8);
+    *reinterpret_cast<u32x4*>(k_pool + page * k_stride_page + (int64_t)g * k_stride_head +
+                              ((int64_t)d * page_size + slot) * 8) = x;
+  }
+  v_pool[page * v_stride_page + (int64_t)g * v_stride_head + (int64_t)d * page_size + slot] =
+      v_new[src + d];
+}
+
+// ------------------------------------------------------------------ launchers
+
+template <int D, int LGP>
+static int launch_attention_dp(const KernelArgs& a, int subtiles, int32_t first_item, int32_t n_items,
+                               hipStream_t stream) {
+  const dim3 grid(n_items), block(W * 64);
+  switch (subtiles) {
+    case 1: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 1>), grid, block, 0, stream, a, first_item); break;
+    case 2: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 2>), grid, block, 0, stream, a, first_item); break;
+    case 3: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 3>), grid, block, 0, stream, a, first_item); break;
+    case 4: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 4>), grid, block, 0, stream, a, first_item); break;
+    default: return OPTIMUS_ERR_INVALID_ARGUMENT;
+  }
+  return OPTIMUS_OK;
+}
+
+template <int D>
+static int launch_attention_d(const optimus_attn_params_t& p, const KernelArgs& a, int subtiles,
+                              int32_t first_item, int32_t n_items, hipStream_t stream) {
+  switch (p.page_size) {
+    case 16: return launch_attention_dp<D, 4>(a, subtiles, first_item, n_items, stream);
+    case 32: return launch_attention_dp<D, 5>(a, subtiles, first_item, n_items, stream);
+    case 64: return launch_attention_dp<D, 6>(a, subtiles, first_item, n_items, stream);
+    case 128: return launch_attention_dp<D, 7>(a, subtiles, first_item, n_items, stream);
+    default: return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
+  }
+}
+
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int subtiles,
+                     int32_t first_item, int32_t n_items, void* stream) {
+  if (n_items <= 0) return OPTIMUS_OK;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int rc;
+  if (p.head_dim == 128) rc = launch_attention_d<128>(p, a, subtiles, first_item, n_items, s);
+  else if (p.head_dim == 64) rc = launch_attention_d<64>(p, a, subtiles, first_item, n_items, s);
+  else return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
+  if (rc != OPTIMUS_OK) return rc;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error((int)e, "attention kernel launch"); return OPTIMUS_ERR_HIP; }
+  return OPTIMUS_OK;
+}
+
+int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges, void* stream) {
+  if (n_merges <= 0) return OPTIMUS_OK;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid(n_merges, kMaxSubtiles), block(256);
+  if (p.head_dim == 128) hipLaunchKernelGGL((merge_kernel<128>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((merge_kernel<64>), grid, block, 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error((int)e, "merge kernel launch"); return OPTIMUS_ERR_HIP; }
+  return OPTIMUS_OK;
+}
+
+int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
+                     const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
+                     const int32_t* token_req, const int32_t* cu_q, const int32_t* prefix_len,
+                     int32_t total_q, void* stream) {
+  if (total_q <= 0) return OPTIMUS_OK;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  int lgp = 0;
+  while ((1 << lgp) < p.page_size) ++lgp;
+  const dim3 grid(total_q, p.num_kv_heads);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL((kv_append_kernel<128>), grid, dim3(128), 0, s, k_pool, v_pool, k_new, v_new,
+                       block_table, token_req, cu_q, prefix_len, p.num_kv_heads, p.page_size, lgp,
+                       p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
+                       p.v_stride_head);
+  else
+    hipLaunchKernelGGL((kv_append_kernel<64>), grid, dim3(64), 0, s, k_pool, v_pool, k_new, v_new,
+                       block_table, token_req, cu_q, prefix_len, p.num_kv_heads, p.page_size, lgp,
+                       p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
+                       p.v_stride_head);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error((int)e, "kv_append kernel launch"); return OPTIMUS_ERR_HIP; }
+  return OPTIMUS_OK;
+}
+
+}  // namespace optimus

@@ -1,0 +1,88 @@
+// Internal structures of the chunked block-diffusion attention library
+// (host planner <-> kernels).  Not part of the C ABI.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "optimus_attn.h"
+
+namespace optimus {
+
+constexpr int kTileTokens = 32;     // keys per MFMA tile step (one 16x16x32 PV contraction)
+constexpr int kRowsPerSubtile = 16; // query rows per MFMA N tile
+constexpr int kMaxSubtiles = 4;     // a work item holds at most 4 x 16 = 64 query rows
+constexpr int kWavesPerBlock = 4;
+
+// One merge job: `n_splits` partials of the same q tile, stored back to back
+// (`row_count` rows each) starting at workspace row `first_part_row`.
+struct MergeItem {
+  int32_t kv_head;
+  int32_t row_begin;
+  int32_t row_count;
+  int32_t q_token0;
+  int32_t first_part_row;
+  int32_t n_splits;
+  int32_t pad0, pad1;
+};
+
+struct Tuning {
+  int32_t target_items = 0;      // 0 -> default from the CU count
+  int32_t min_split_tokens = 0;  // 0 -> default
+  int32_t max_split_tokens = 0;  // 0 -> default
+};
+
+// Result of host planning for one iteration.
+struct HostPlan {
+  int32_t batch = 0;
+  int32_t total_q = 0;
+  std::vector<optimus_work_item_t> items;  // sorted by subtile class, then cost
+  int32_t class_begin[kMaxSubtiles + 1] = {0, 0, 0, 0, 0};  // items of class nt: [class_begin[nt-1], class_begin[nt])
+  std::vector<MergeItem> merges;
+  std::vector<int32_t> token_req;   // [T] request of each query token
+  std::vector<int32_t> cu_q, prefix_len, block_start;
+  int64_t part_rows = 0;            // rows of split-KV partials in the workspace
+  size_t workspace_bytes = 0;
+};
+
+// Pure host code: validate the descriptors and build the work list.
+// Returns an optimus_status_t.
+int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int num_cus,
+                    int32_t batch, const int32_t* cu_q, const int32_t* prefix_len,
+                    const int32_t* block_start, const int32_t* block_table, HostPlan* out);
+
+int validate_params(const optimus_attn_params_t& p);
+
+// Device-side argument block shared by the kernels.
+struct KernelArgs {
+  const uint16_t* q;
+  const uint16_t* k_pool;
+  const uint16_t* v_pool;
+  const int32_t* block_table;
+  const optimus_work_item_t* items;
+  const MergeItem* merges;
+  const int32_t* prefix_len;
+  const int32_t* block_start;
+  void* out;
+  float* ws_o;    // [part_rows, D]
+  float* ws_ml;   // [part_rows, 2]  (running max in log2 units, sum)
+  int64_t k_stride_page, k_stride_head, v_stride_page, v_stride_head;
+  int32_t num_q_heads, group, max_pages_per_req, out_fp32;
+  int32_t mask_mode, block_size;
+  float scale_log2;  // softmax scale * log2(e)
+};
+
+// Kernel launchers (kernels.hip).  `stream` is a hipStream_t.
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int subtiles,
+                     int32_t first_item, int32_t n_items, void* stream);
+int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges,
+                 void* stream);
+int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
+                     const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
+                     const int32_t* token_req, const int32_t* cu_q, const int32_t* prefix_len,
+                     int32_t total_q, void* stream);
+
+void set_hip_error(int hip_err, const char* where);
+
+}  // namespace optimus

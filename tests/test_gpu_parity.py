@@ -1,0 +1,261 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle.
+
+Bar: bf16 in, fp32 accumulate, bf16 out: max |err| <= 1e-2 and mean |err| <= 1e-3 over
+the outputs of a case; pool contents after the append and everything derived from the
+block table bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_24832_amd import inputs
+from tests import hip_path as hp
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def full_parity(oracle, w, what, **kw):
+    bits = hp.host_bits(w)  # before the append
+    out, plan = hp.run_hip(w, **kw)
+    ref, _, _ = hp.run_oracle(oracle, w, bits=bits, **{k: v for k, v in kw.items() if k == "mask_mode"})
+    mx, mean = hp.check_close(out.float().cpu().numpy(), ref, what=what)
+    _say(f"{what}: items={plan.num_work_items()} merges={plan.num_merge_items()} "
+         f"max={mx:.2e} mean={mean:.2e}")
+    # append bit-exactness against the oracle's scatter
+    p = hp.oracle_params(oracle, w)
+    kp, vp = bits["k_pool"].copy(), bits["v_pool"].copy()
+    oracle.kv_append(p, w.cu_q, w.prefix_len, w.block_table, bits["k_new"], bits["v_new"], kp, vp)
+    np.testing.assert_array_equal(inputs.to_bits(w.k_pool), kp)
+    np.testing.assert_array_equal(inputs.to_bits(w.v_pool), vp)
+    return out, plan
+
+
+def test_config0_tiny(oracle_mod):
+    _say("config0")
+    w = inputs.make_config(0, device=DEV)
+    full_parity(oracle_mod, w, "config0")
+
+
+@pytest.mark.parametrize("c", [4, 8, 16, 32])
+def test_config1_mha_batch1(oracle_mod, c):
+    _say(f"config1 c={c}")
+    w = inputs.make_config(1, device=DEV, chunk=c)
+    _, plan = full_parity(oracle_mod, w, f"config1 c={c}")
+    assert plan.num_merge_items() > 0  # batch 1 must split the KV range to fill the chip
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 5, 6, 7, 22, 31, 32])
+def test_arbitrary_chunk_sizes(oracle_mod, c):
+    """Any chunk size, not only 1 or the block size (Sec. 6); Sec. 7.4 reports 6 and 22."""
+    _say(f"chunk {c}")
+    w = inputs.make_workload("chunks", seed=100 + c, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[200, 77, 1000],
+                             chunk=[c, c, c], block_inner=[0, 0, 0], device=DEV)
+    full_parity(oracle_mod, w, f"chunk {c}")
+
+
+def test_ragged_edge_cases(oracle_mod):
+    """L=0, c=0, one-key tail tiles, tile-aligned lengths, a request with one key in total."""
+    _say("ragged edges")
+    L = [0, 0, 31, 32, 33, 63, 64, 65, 16, 15, 1, 0, 511, 96]
+    c = [1, 5, 1, 1, 1, 1, 1, 1, 0, 1, 31, 0, 1, 32]
+    w = inputs.make_workload("edges", seed=7, num_q_heads=8, num_kv_heads=4, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=L, chunk=c,
+                             block_inner=[0] * len(L), device=DEV)
+    out, _ = full_parity(oracle_mod, w, "ragged edges")
+    # L=0, c=1: the only key is the token itself
+    t = int(w.cu_q[0])
+    g = w.num_q_heads // w.num_kv_heads
+    np.testing.assert_array_equal(out[t].float().cpu().numpy(),
+                                  w.v_new[t].float().cpu().numpy().repeat(g, axis=0))
+
+
+@pytest.mark.parametrize("P", [16, 32, 64, 128])
+@pytest.mark.parametrize("D", [64, 128])
+def test_page_sizes_and_head_dims(oracle_mod, P, D):
+    _say(f"P={P} D={D}")
+    w = inputs.make_workload("pd", seed=11 + P + D, num_q_heads=6, num_kv_heads=2, head_dim=D,
+                             page_size=P, block_size=32, prefix_len=[300, 45, 129, 0],
+                             chunk=[7, 32, 1, 3], block_inner=[0, 0, 0, 0], device=DEV)
+    full_parity(oracle_mod, w, f"P={P} D={D}")
+
+
+def test_gqa7_many_q_tiles(oracle_mod):
+    """G=7, c=32 -> 224 rows per kv head: four q tiles, odd head grouping."""
+    _say("gqa7")
+    w = inputs.make_workload("gqa7", seed=13, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[700, 130], chunk=[32, 9],
+                             block_inner=[0, 0], device=DEV)
+    full_parity(oracle_mod, w, "gqa7")
+
+
+def test_forced_splits_and_merge(oracle_mod):
+    """Tiny split size: many partials per row, including splits some waves get no tile of."""
+    _say("forced splits")
+    w = inputs.make_workload("splits", seed=17, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[1000, 50, 333], chunk=[4, 20, 1],
+                             block_inner=[0, 0, 0], device=DEV)
+    for split in (32, 64, 96):
+        w2 = hp.clone_workload(w)
+        _, plan = full_parity(oracle_mod, w2, f"split {split}",
+                              tuning=dict(target_items=1 << 20, min_split_tokens=split,
+                                          max_split_tokens=split))
+        assert plan.num_merge_items() > 0
+    # and no split at all
+    w2 = hp.clone_workload(w)
+    _, plan = full_parity(oracle_mod, w2, "unsplit",
+                          tuning=dict(target_items=1, min_split_tokens=1 << 20, max_split_tokens=1 << 20))
+    assert plan.num_merge_items() == 0
+
+
+def test_fp32_output(oracle_mod):
+    _say("fp32 out")
+    w = inputs.make_config(0, device=DEV)
+    bits = hp.host_bits(w)
+    out, _ = hp.run_hip(w, out_dtype=1)
+    ref, _, _ = hp.run_oracle(oracle_mod, w, bits=bits)
+    mx, mean = hp.check_close(out.cpu().numpy(), ref, max_tol=5e-3, mean_tol=5e-4, what="fp32 out")
+    _say(f"fp32 out: max={mx:.2e} mean={mean:.2e}")
+
+
+def test_block_causal_mode(oracle_mod):
+    """mask_mode 1: chunks that cross a block boundary, block-causal inside the chunk."""
+    _say("mask mode 1")
+    w = inputs.make_workload("obs", seed=19, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[100, 40, 0, 500],
+                             chunk=[32, 32, 20, 7], block_inner=[20, 0, 0, 30], mask_mode=1,
+                             device=DEV)
+    full_parity(oracle_mod, w, "mask mode 1")
+    w2 = inputs.make_workload("obs", seed=19, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                              page_size=16, block_size=32, prefix_len=[100, 40, 0, 500],
+                              chunk=[32, 32, 20, 7], block_inner=[20, 0, 0, 30], mask_mode=1,
+                              device=DEV)
+    full_parity(oracle_mod, w2, "mask mode 1 split",
+                tuning=dict(target_items=1 << 20, min_split_tokens=32, max_split_tokens=32))
+
+
+def test_strided_interleaved_pool(oracle_mod):
+    """K and V tiles interleaved in one allocation: page/head strides twice the dense ones."""
+    _say("strided pool")
+    w = inputs.make_workload("strided", seed=23, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[150, 61], chunk=[5, 16],
+                             block_inner=[0, 0], device=DEV)
+    tile = w.page_size * w.head_dim
+    Hkv = w.num_kv_heads
+    both = torch.full((w.num_pages, Hkv, 2, tile), float("nan"), dtype=torch.bfloat16, device=DEV)
+    both[:, :, 0] = w.k_pool
+    both[:, :, 1] = w.v_pool
+    bits = hp.host_bits(w)
+    ref, _, _ = hp.run_oracle(oracle_mod, w, bits=bits)
+    w.k_pool = both.view(-1)[0:]
+    w.v_pool = both.view(-1)[tile:]
+    out, _ = hp.run_hip(w, k_stride_page=2 * Hkv * tile, v_stride_page=2 * Hkv * tile,
+                        k_stride_head=2 * tile, v_stride_head=2 * tile)
+    hp.check_close(out.float().cpu().numpy(), ref, what="strided pool")
+
+
+def test_gpu_invariants(oracle_mod):
+    """Page reshuffle and NaN tails leave the GPU output bit-identical; chunk permutation
+    permutes it within tolerance."""
+    _say("invariants")
+    kw = dict(seed=29, num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16, block_size=32,
+              prefix_len=[300, 37], chunk=[6, 11], block_inner=[0, 0], device=DEV)
+    clean = inputs.make_workload("inv", poison=False, **kw)
+    dirty = inputs.make_workload("inv", poison=True, **kw)
+    o_clean, _ = hp.run_hip(clean)
+    o_dirty, _ = hp.run_hip(dirty)
+    assert torch.isfinite(o_dirty.float()).all()
+    assert torch.equal(o_clean, o_dirty)
+    # reshuffle physical pages
+    base = inputs.make_workload("inv", poison=True, **kw)
+    rng = np.random.RandomState(1)
+    perm = rng.permutation(base.num_pages)
+    inv = torch.as_tensor(np.argsort(perm), device=DEV)
+    shuf = hp.clone_workload(base)
+    shuf.k_pool = base.k_pool[inv].contiguous()
+    shuf.v_pool = base.v_pool[inv].contiguous()
+    bt = base.block_table.copy()
+    bt[bt >= 0] = perm[bt[bt >= 0]]
+    shuf.block_table = bt
+    o_shuf, _ = hp.run_hip(shuf)
+    assert torch.equal(o_shuf, o_dirty)
+    # permute chunk tokens
+    pm = np.concatenate([rng.permutation(6), 6 + rng.permutation(11)])
+    pt = torch.as_tensor(pm, device=DEV)
+    permd = inputs.make_workload("inv", poison=True, **kw)
+    permd.q, permd.k_new, permd.v_new = permd.q[pt].contiguous(), permd.k_new[pt].contiguous(), \
+        permd.v_new[pt].contiguous()
+    o_perm, _ = hp.run_hip(permd)
+    hp.check_close(o_perm.float().cpu().numpy(), o_dirty[pt].double().cpu().numpy(), what="perm")
+
+
+def test_constant_v_and_single_token_decode(oracle_mod):
+    _say("constant V")
+    w = inputs.make_workload("cv", seed=31, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[500, 40], chunk=[1, 1],
+                             block_inner=[0, 0], poison=False, device=DEV)
+    v0 = torch.linspace(-1.5, 2.0, 128, device=DEV).to(torch.bfloat16)
+    inputs.v_tile_view(w.v_pool, 16, 128, 1)[:] = v0.view(1, 1, 128, 1)
+    w.v_new[:] = v0
+    out, _ = hp.run_hip(w)
+    err = (out.float() - v0.float()).abs().max().item()
+    assert err <= 2.0 * 2 ** -8, err  # one bf16 rounding of |v| <= 2
+
+
+def test_empty_batches():
+    _say("empty")
+    w = inputs.make_workload("empty", seed=37, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=32, prefix_len=[50, 20], chunk=[0, 0],
+                             device=DEV)
+    out, plan = hp.run_hip(w)
+    assert out.shape[0] == 0 and plan.num_work_items() == 0
+    from paper_2605_24832_amd import Plan
+    plan = Plan(hp.params_of(w), device=0)
+    assert plan.plan_update([0], [], []) == 0
+    plan.attn_forward(None, None, None, None, None)  # no-op on an empty plan
+
+
+def sampled_parity(oracle, w, what, requests, kv_heads=None):
+    """Full-size launch; oracle on a sample of requests (and kv-head groups)."""
+    _say(f"{what}: generating host copy")
+    bits = hp.host_bits(w)
+    out, plan = hp.run_hip(w)
+    _say(f"{what}: hip done, items={plan.num_work_items()} merges={plan.num_merge_items()}")
+    ref, tok, qh = hp.run_oracle(oracle, w, bits=bits, requests=requests, kv_heads=kv_heads)
+    got = out[torch.as_tensor(tok, device=DEV)][:, torch.as_tensor(qh, device=DEV)]
+    mx, mean = hp.check_close(got.float().cpu().numpy(), ref, what=what)
+    _say(f"{what}: sampled rows={ref.shape[0]} heads={ref.shape[1]} max={mx:.2e} mean={mean:.2e}")
+    # properties that hold at any size: finite everywhere, every output written
+    assert torch.isfinite(out.float()).all()
+    return out
+
+
+def test_config2_gqa_continuous_batching(oracle_mod):
+    w = inputs.make_config(2, device=DEV)
+    rng = np.random.RandomState(2)
+    req = sorted(rng.choice(w.batch, size=12, replace=False).tolist())
+    # make sure the sample holds the largest chunk and the longest prefix
+    req = sorted(set(req) | {int(np.argmax(w.chunk)), int(np.argmax(w.prefix_len))})
+    sampled_parity(oracle_mod, w, "config2", req)
+
+
+def test_config3_high_load(oracle_mod):
+    w = inputs.make_config(3, device=DEV)
+    assert w.k_pool.numel() * 2 > (1 << 31)  # the pool crosses the 32-bit byte-offset range
+    rng = np.random.RandomState(3)
+    req = sorted(set(rng.choice(w.batch, size=6, replace=False).tolist()) |
+                 {int(np.argmax(w.prefix_len)), int(np.argmax(w.block_table.max(axis=1)))})
+    sampled_parity(oracle_mod, w, "config3", req)
+
+
+@pytest.mark.parametrize("chunk", [64, 128, None])
+def test_config4_long_context(oracle_mod, chunk):
+    w = inputs.make_config(4, device=DEV, chunk=chunk)
+    assert w.extra["peaked_positions"] > 0
+    sampled_parity(oracle_mod, w, f"config4 chunk={chunk}", requests=[1], kv_heads=[5])

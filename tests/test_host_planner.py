@@ -1,0 +1,211 @@
+"""CPU tests of the C-ABI library's host side: exports, validation, work-list coverage.
+
+No compute call is made: plans are created host-only (device = -1).
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_24832_amd import AttnParams, OptimusError, Plan, binding, inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def make_params(**kw):
+    args = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, block_size=32,
+                num_pages=100000, max_pages_per_req=1024)
+    args.update(kw)
+    return AttnParams(**args)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    header = open(os.path.join(ROOT, "include", "optimus_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)  # declarations only, no comments
+    declared = set(re.findall(r"\b(optimus_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations parsed"
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    for s in range(0, -12, -1):
+        assert binding.status_string(s) != "unknown status"
+    assert binding.status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("bad,code", [
+    (dict(num_q_heads=30), -2), (dict(head_dim=96), -2), (dict(page_size=8), -2),
+    (dict(kv_layout=0), -2), (dict(mask_mode=2), -1), (dict(out_dtype=3), -1),
+    (dict(block_size=0), -1), (dict(k_stride_head=100), -1), (dict(k_stride_page=1024), -1),
+])
+def test_plan_create_rejects_bad_params(bad, code):
+    with pytest.raises(OptimusError) as e:
+        Plan(make_params(**bad), device=-1)
+    assert e.value.status == code
+
+
+def test_plan_update_error_codes():
+    plan = Plan(make_params(max_pages_per_req=8, num_pages=50), device=-1)
+    ok = dict(cu_q=[0, 4, 6], prefix_len=[60, 20], block_start=[32, 0])
+    bt = np.full((2, 8), -1, dtype=np.int32)
+    bt[0, :4] = [3, 9, 1, 7]
+    bt[1, :2] = [49, 0]
+    assert plan.plan_update(block_table=bt, **ok) >= 0
+
+    def expect(code, **kw):
+        args = dict(ok, block_table=bt)
+        args.update(kw)
+        with pytest.raises(OptimusError) as e:
+            plan.plan_update(**args)
+        assert e.value.status == code, (e.value.status, kw)
+
+    expect(-3, cu_q=[1, 4, 6])
+    expect(-3, cu_q=[0, 4, 3])
+    expect(-4, prefix_len=[-1, 20])
+    expect(-4, block_start=[61, 0])
+    expect(-4, block_start=[-1, 0])
+    expect(-5, block_start=[28, 0])          # d=32 plus c=4 leaves the block of 32
+    expect(-5, cu_q=[0, 4, 40], prefix_len=[60, 0])  # c=36 > B
+    expect(-6, prefix_len=[60, 127], block_start=[32, 127])  # 129 slots need 9 pages > 8
+    bt2 = bt.copy(); bt2[0, 3] = 50
+    expect(-7, block_table=bt2)
+    bt3 = bt.copy(); bt3[1, 1] = -1
+    expect(-7, block_table=bt3)
+    # a failed update leaves the plan unplanned
+    with pytest.raises(OptimusError) as e:
+        plan.kv_append(None, None, None, None, None)
+    assert e.value.status == -9
+    # device calls on a host-only plan
+    plan.plan_update(block_table=bt, **ok)
+    with pytest.raises(OptimusError) as e:
+        plan.kv_append(None, None, None, None, None)
+    assert e.value.status == -10
+
+
+def test_block_table_too_short_boundary():
+    plan = Plan(make_params(max_pages_per_req=8), device=-1)
+    plan.plan_update([0, 2], [126], [126])            # 128 slots = 8 pages: fits
+    with pytest.raises(OptimusError) as e:
+        plan.plan_update([0, 3], [126], [126])        # 129 slots = 9 pages
+    assert e.value.status == -6
+
+
+def coverage_check(plan, p: AttnParams, cu_q, prefix_len):
+    """Every (request, kv head, row, key) is covered exactly once; partial rows are disjoint."""
+    items = plan.work_items()
+    G = p.num_q_heads // p.num_kv_heads
+    c = np.diff(cu_q)
+    assert (items["row_count"] >= 1).all() and (items["row_count"] <= 64).all()
+    assert (items["kv_begin"] % 32 == 0).all()
+    assert (items["kv_begin"] < items["kv_end"]).all()
+    part_rows = []
+    for i in range(len(prefix_len)):
+        kv_len = int(prefix_len[i] + c[i])
+        rows = int(c[i]) * G
+        mine = items[items["req"] == i]
+        if c[i] == 0:
+            assert len(mine) == 0
+            continue
+        assert (mine["q_token0"] == cu_q[i]).all()
+        assert (mine["kv_end"] <= kv_len).all()
+        for g in range(p.num_kv_heads):
+            cover = np.zeros((rows, kv_len), dtype=np.int32)
+            sub = mine[mine["kv_head"] == g]
+            for it in sub:
+                r0, rc = int(it["row_begin"]), int(it["row_count"])
+                assert r0 + rc <= rows
+                cover[r0:r0 + rc, int(it["kv_begin"]):int(it["kv_end"])] += 1
+                if it["part_row"] >= 0:
+                    part_rows.append((int(it["part_row"]), rc))
+            assert (cover == 1).all(), f"request {i} head {g}: coverage not exactly once"
+            # a q tile is either one unsplit item writing the output or >= 2 partial items
+            for r0 in np.unique(sub["row_begin"]):
+                tile = sub[sub["row_begin"] == r0]
+                if len(tile) == 1:
+                    assert tile[0]["part_row"] == -1
+                else:
+                    assert (tile["part_row"] >= 0).all()
+    part_rows.sort()
+    end = 0
+    for start, n in part_rows:
+        assert start >= end, "partial rows overlap"
+        end = start + n
+    assert plan.workspace_bytes == end * (p.head_dim + 2) * 4
+    return items
+
+
+@pytest.mark.parametrize("k", [0, 1, 2, 3])
+def test_work_list_covers_each_config_exactly_once(k):
+    shapes = {0: dict(num_q_heads=4, num_kv_heads=4, head_dim=64),
+              1: dict(num_q_heads=32, num_kv_heads=32),
+              2: dict(num_q_heads=28, num_kv_heads=4),
+              3: dict(num_q_heads=32, num_kv_heads=8)}[k]
+    rng = np.random.RandomState(inputs.BASE_SEED + k)
+    if k == 0:
+        L, c = np.array([128]), np.array([8])
+    elif k == 1:
+        L, c = np.array([2048]), np.array([32])
+    elif k == 2:
+        L, c = rng.randint(512, 4097, size=64), rng.choice([1, 2, 4, 8, 16, 32], size=64)
+    else:
+        L, c = rng.randint(1024, 8193, size=48), rng.choice([1, 2, 4], size=48)
+    cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    p = make_params(**shapes)
+    plan = Plan(p, device=-1)
+    plan.plan_update(cu, L, L - np.minimum(L % 32, 32 - c))
+    items = coverage_check(plan, p, cu, L)
+    assert len(items) == plan.num_work_items()
+
+
+def test_work_list_with_forced_tuning_and_odd_shapes():
+    p = make_params(num_q_heads=28, num_kv_heads=4, block_size=32)
+    plan = Plan(p, device=-1)
+    L = np.array([0, 31, 32, 33, 1000, 7, 64])
+    c = np.array([5, 1, 0, 32, 17, 25, 32])
+    cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    for tuning in (dict(target_items=1 << 20, min_split_tokens=32, max_split_tokens=32),
+                   dict(target_items=1, min_split_tokens=1 << 20, max_split_tokens=1 << 20),
+                   dict(target_items=100, min_split_tokens=64, max_split_tokens=256), dict()):
+        plan.set_tuning(**tuning)
+        plan.plan_update(cu, L, L)  # d_i = 0
+        coverage_check(plan, p, cu, L)
+    with pytest.raises(OptimusError):
+        plan.set_tuning(min_split_tokens=33)
+
+
+def test_plan_is_deterministic_and_longest_first_within_class():
+    p = make_params()
+    rng = np.random.RandomState(5)
+    L = rng.randint(1024, 8193, size=32)
+    c = rng.choice([1, 2, 4, 8], size=32)
+    cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    a = Plan(p, device=-1)
+    b = Plan(p, device=-1)
+    a.plan_update(cu, L, L)
+    b.plan_update(cu, L, L)
+    ia, ib = a.work_items(), b.work_items()
+    assert (ia == ib).all()
+    nt = (ia["row_count"] + 15) // 16
+    assert (np.diff(nt) >= 0).all()  # grouped by subtile class
+    for cls in np.unique(nt):
+        tiles = (ia["kv_end"] - ia["kv_begin"] + 31)[nt == cls] // 32
+        assert (np.diff(tiles) <= 0).all()
+
+
+def test_empty_batch_and_zero_chunks():
+    plan = Plan(make_params(), device=-1)
+    assert plan.plan_update([0], [], []) == 0
+    assert plan.num_work_items() == 0
+    assert plan.plan_update([0, 0, 0], [10, 20], [10, 20]) == 0
+    assert plan.num_work_items() == 0
+
+
+def test_header_struct_sizes_match_binding():
+    assert ctypes.sizeof(binding.WorkItem) == 32
+    # 12 int32/float fields + 4 int64
+    assert ctypes.sizeof(binding._CParams) == 12 * 4 + 4 * 8
