@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked block-diffusion attention step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: host planning
+(plan_update), KV append, attention forward, split-KV merge, all through the C ABI.
+The inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others]
+
+Workloads: tiny, mha_b1_c{4,8,16,32}, gqa_cb64, highload_b256 (default), longctx_b4_c{64,128},
+longctx_b4_mix.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+INFINITY_CACHE_BYTES = 256 << 20
+
+
+def parse_workload(name: str):
+    """name -> (config index, chunk or None)."""
+    if name == "tiny":
+        return 0, None
+    if name.startswith("mha_b1"):
+        return 1, int(name.split("_c")[1]) if "_c" in name else 32
+    if name == "gqa_cb64":
+        return 2, None
+    if name == "highload_b256":
+        return 3, None
+    if name.startswith("longctx_b4"):
+        if name.endswith("mix") or name == "longctx_b4":
+            return 4, None
+        return 4, int(name.split("_c")[1])
+    raise SystemExit(f"unknown workload {name!r}")
+
+
+WORKLOAD_TEXT = {
+    0: "configs[0] tiny: R=1 Hq=Hkv=4 D=64 L=128 c=8 P=16",
+    1: "configs[1] MHA batch 1: Hq=Hkv=32 D=128 L=2048 B=32 P=16",
+    2: "configs[2] GQA continuous batching: R=64 Hq=28 Hkv=4 D=128 L~U[512,4096] c~U{1,2,4,8,16,32} P=16 shuffled pool",
+    3: "configs[3] high-load memory-bound: R=256 Hq=32 Hkv=8 D=128 L~U[1024,8192] c~U{1,2,4} P=16 permuted pool",
+    4: "configs[4] long-context: R=4 Hq=32 Hkv=8 D=128 L=32768 B=128 P=64 K x2 on 1% of positions",
+}
+
+
+class Runner:
+    """Device state of one workload: rotating pool copies, plan, output, workspace."""
+
+    def __init__(self, w, copies: int):
+        import torch
+        from paper_2605_24832_amd import AttnParams, Plan
+        self.torch = torch
+        self.w = w
+        dev = w.q.device
+        self.plan = Plan(AttnParams(num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                                    head_dim=w.head_dim, page_size=w.page_size,
+                                    block_size=w.block_size, num_pages=w.num_pages,
+                                    max_pages_per_req=w.block_table.shape[1],
+                                    mask_mode=w.mask_mode), device=dev.index or 0)
+        self.bt = torch.as_tensor(w.block_table, device=dev)
+        # rotate over independent copies of the pools so that a small workload is not
+        # served out of the memory-side cache
+        self.pools = [(w.k_pool, w.v_pool)]
+        for _ in range(copies - 1):
+            self.pools.append((w.k_pool.clone(), w.v_pool.clone()))
+        self.out = torch.empty_like(w.q)
+        ws_bytes = self.plan.plan_update(w.cu_q, w.prefix_len, w.block_start, w.block_table)
+        self.ws = torch.empty(ws_bytes // 4 + 4, dtype=torch.float32, device=dev)
+        self.step_no = 0
+
+    def step(self, replan: bool = True):
+        w = self.w
+        kp, vp = self.pools[self.step_no % len(self.pools)]
+        self.step_no += 1
+        if replan:
+            # block-table validation is part of planning; the table itself is already on the device
+            self.plan.plan_update(w.cu_q, w.prefix_len, w.block_start, w.block_table)
+        self.plan.kv_append(kp, vp, w.k_new, w.v_new, self.bt)
+        self.plan.attn_forward(w.q, kp, vp, self.bt, self.out, self.ws)
+
+    def timed(self, steps: int, warmup: int, replan: bool = True):
+        """-> (ms per step wall, ms per step of the attention main kernel by HIP events)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(replan)
+        torch.cuda.synchronize()
+        self.plan.set_timing(True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(replan)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kern_ms, n = self.plan.timing_read()
+        self.plan.set_timing(False)
+        return (t1 - t0) * 1e3 / steps, kern_ms / max(n, 1)
+
+
+def copies_for(w) -> int:
+    foot = w.kv_bytes()
+    if foot >= 4 * INFINITY_CACHE_BYTES:
+        return 1
+    return int(min(32, max(2, -(-2 * INFINITY_CACHE_BYTES // max(foot, 1)))))
+
+
+def measure(cfg: int, chunk, steps: int, warmup: int, device: str):
+    from paper_2605_24832_amd import inputs
+    w = inputs.make_config(cfg, device=device, chunk=chunk)
+    r = Runner(w, copies_for(w))
+    ms, kern_ms = r.timed(steps, warmup, replan=True)
+    ms_np, _ = r.timed(max(3, steps // 2), 1, replan=False)
+    # host cost of planning alone
+    t0 = time.perf_counter()
+    for _ in range(5):
+        r.plan.plan_update(w.cu_q, w.prefix_len, w.block_start, w.block_table)
+    plan_ms = (time.perf_counter() - t0) * 1e3 / 5
+    alg_bytes = w.kv_bytes() + w.qo_bytes()
+    res = {
+        "workload": w.name, "ms_per_step": ms, "ms_per_step_plan_excluded": ms_np,
+        "plan_update_host_ms": plan_ms, "attn_kernel_ms": kern_ms,
+        "query_tokens": w.total_q, "tokens_per_s": w.total_q / (ms * 1e-3),
+        "algorithmic_bytes": alg_bytes, "flops": w.flops(),
+        "hbm_GBs": alg_bytes / (kern_ms * 1e-3) / 1e9,
+        "tflops": w.flops() / (kern_ms * 1e-3) / 1e12,
+        "work_items": r.plan.num_work_items(), "merge_items": r.plan.num_merge_items(),
+        "pool_copies_rotated": len(r.pools),
+    }
+    return w, r, res
+
+
+def cpu_baseline(w, runner, budget_s: float = 15.0):
+    """Time the fp64 oracle on a bounded sample of the same workload and check the GPU
+    output of those requests against it."""
+    import numpy as np
+
+    import oracle
+    from paper_2605_24832_amd import inputs
+    torch = runner.torch
+    bits = {k: inputs.to_bits(getattr(w, k)) for k in ("q", "k_new", "v_new")}
+    # the pool of the last step (chunk K/V appended; the oracle takes chunk rows from k_new)
+    kp, vp = runner.pools[(runner.step_no - 1) % len(runner.pools)]
+    bits["k_pool"], bits["v_pool"] = inputs.to_bits(kp), inputs.to_bits(vp)
+    gpu_out = runner.out.float().cpu().numpy().astype(np.float64)
+    p = oracle.make_params(num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                           head_dim=w.head_dim, page_size=w.page_size, block_size=w.block_size,
+                           max_pages_per_req=w.block_table.shape[1], mask_mode=w.mask_mode,
+                           kv_layout=w.kv_layout)
+
+    def run(req):
+        tok = np.concatenate([np.arange(w.cu_q[i], w.cu_q[i + 1]) for i in req])
+        cu = np.zeros(len(req) + 1, dtype=np.int32)
+        cu[1:] = np.cumsum(w.chunk[req])
+        t0 = time.perf_counter()
+        ref = oracle.chunked_attention(p, cu, w.prefix_len[req], w.block_start[req],
+                                       w.block_table[req], bits["q"].reshape(-1, w.num_q_heads, w.head_dim)[tok],
+                                       bits["k_new"].reshape(-1, w.num_kv_heads, w.head_dim)[tok],
+                                       bits["v_new"].reshape(-1, w.num_kv_heads, w.head_dim)[tok],
+                                       bits["k_pool"], bits["v_pool"])
+        return time.perf_counter() - t0, ref, tok
+
+    order = np.arange(w.batch)
+    cost = (w.chunk.astype(np.int64) * (w.prefix_len + w.chunk))
+    # calibrate on a few requests, then extend to fill the time budget
+    n0 = min(w.batch, max(1, oracle.num_threads() // max(1, w.num_q_heads) + 1))
+    dt0, ref, tok = run(order[:n0])
+    rate = max(cost[:n0].sum(), 1) / max(dt0, 1e-6)
+    n = n0
+    while n < w.batch and cost[:n + 1].sum() / rate < budget_s:
+        n += 1
+    if n > n0:
+        dt, ref, tok = run(order[:n])
+    else:
+        dt = dt0
+    err = np.abs(gpu_out[tok] - ref)
+    return {
+        "value": float(len(tok) / dt), "unit": "tokens/s", "cores": int(oracle.num_threads()),
+        "kind": "oracle",
+        "sample": f"requests 0..{n - 1} of {w.name} ({len(tok)} of {w.total_q} query tokens, "
+                  f"{dt:.2f} s of fp64 CPU work)",
+    }, {"max_abs_err": float(err.max()), "mean_abs_err": float(err.mean()),
+        "checked_tokens": int(len(tok))}
+
+
+def load_traffic(workload: str):
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        t = json.load(f)
+    e = t.get(workload)
+    return None if e is None else e.get("hbm_bytes_per_launch")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="highload_b256")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (torch copy kernel), the known-size "
+                         "reference that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+                         "use --gpus 1")
+    import torch
+    from paper_2605_24832_amd import load_library
+    load_library()  # no fallback: fail here if the HIP library is missing
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    dev = "cuda:0"
+    cfg, chunk = parse_workload(args.workload)
+    w, runner, res = measure(cfg, chunk, args.steps, args.warmup, dev)
+
+    bound_mfma = cfg == 4
+    if bound_mfma:
+        roofline = {"bound": "mfma", "achieved": res["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": res["tflops"] / MFMA_BF16_PEAK_TFLOPS}
+    else:
+        roofline = {"bound": "hbm", "achieved": res["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": res["hbm_GBs"] / HBM_PEAK_GBS}
+    roofline["traffic"] = load_traffic(w.name)
+    roofline["kernel"] = "attn_split_wave_kernel"
+    roofline["kernel_ms"] = res["attn_kernel_ms"]
+    roofline["algorithmic_bytes_per_launch"] = res["algorithmic_bytes"]
+    roofline["flops_per_launch"] = res["flops"]
+
+    line = {
+        "metric": "query tokens/s, chunked block-diffusion attention step (plan + KV append + attention + merge)",
+        "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {WORKLOAD_TEXT[cfg]}", "batch": w.batch,
+                   "query_tokens": w.total_q, "kv_tokens": int((w.prefix_len + w.chunk).sum()),
+                   "pool_copies_rotated": res["pool_copies_rotated"]},
+        "roofline": roofline,
+        "attention_tflops": res["tflops"], "achieved_hbm_TBs": res["hbm_GBs"] / 1e3,
+        "ms_per_step_plan_excluded": res["ms_per_step_plan_excluded"],
+        "plan_update_host_ms": res["plan_update_host_ms"],
+        "work_items": res["work_items"], "merge_items": res["merge_items"],
+    }
+    if not args.no_cpu_baseline:
+        base, parity = cpu_baseline(w, runner)
+        line["cpu_baseline"] = base
+        line["parity_vs_oracle"] = parity
+    del runner, w
+    torch.cuda.empty_cache()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        line["copy_calibration"] = {"bytes_read_per_copy": src.numel() * 2,
+                                    "bytes_written_per_copy": src.numel() * 2, "copies": 3}
+        del src, dst
+        torch.cuda.empty_cache()
+
+    if not args.no_others:
+        others = []
+        for name in ("mha_b1_c4", "mha_b1_c32", "gqa_cb64", "highload_b256", "longctx_b4_c64",
+                     "longctx_b4_c128"):
+            if name == args.workload:
+                continue
+            c2, ch2 = parse_workload(name)
+            w2, r2, o = measure(c2, ch2, max(5, args.steps // 3), 3, dev)
+            o["roofline_frac_hbm"] = o["hbm_GBs"] / HBM_PEAK_GBS
+            o["roofline_frac_mfma_bf16"] = o["tflops"] / MFMA_BF16_PEAK_TFLOPS
+            others.append(o)
+            del w2, r2
+            torch.cuda.empty_cache()
+        line["other_configs"] = others
+    line["paper_context"] = ("the paper reports no kernel-level number for this path; its system "
+                             "results (A100-80GB, FP16) are not comparable")
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -111,9 +111,11 @@ int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
  *   block_start_host [batch]   s_i, 0 <= s_i <= L_i, origin of the current block
  *   block_table_host [batch, max_pages_per_req] or NULL (skips page-id checks)
  *   workspace_bytes_out  bytes of scratch that optimus_attn_forward needs
- * Must not be called while a forward of the same plan from TWO updates ago is
- * still running (the device work list is double-buffered).  batch == 0 is a
- * valid no-op plan.                                                            */
+ * The upload of the work list is enqueued by the next kv_append / forward on
+ * that call's stream, behind the kernels of earlier iterations, so updates may
+ * run ahead of the device as long as one plan is used on one stream at a time
+ * (the host blocks only when it is four updates ahead).  batch == 0 is a valid
+ * no-op plan.                                                                  */
 int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch,
                              const int32_t* cu_q_host, const int32_t* prefix_len_host,
                              const int32_t* block_start_host,
@@ -154,11 +156,13 @@ int optimus_attn_plan_set_tuning(optimus_attn_plan_t* plan, int32_t target_items
                                  int32_t min_split_tokens, int32_t max_split_tokens);
 
 /* Optional timing of the attention main kernel with HIP events recorded on the
- * caller's stream around its launch.  enable != 0 turns recording on for later
- * forwards; optimus_attn_last_kernel_ms synchronises on the last end event and
- * returns the elapsed milliseconds (negative status if none was recorded).     */
+ * caller's stream around its launch(es) in every forward.  set_timing(enable
+ * != 0) clears the record and turns recording on; timing_read synchronises on
+ * the recorded events and returns the summed milliseconds and the number of
+ * forwards recorded since then (at most 4096 are kept; later ones are dropped). */
 int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable);
-int optimus_attn_last_kernel_ms(optimus_attn_plan_t* plan, float* ms_out);
+int optimus_attn_timing_read(optimus_attn_plan_t* plan, float* total_ms_out,
+                             int32_t* forwards_out);
 
 const char* optimus_status_string(int status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */

@@ -21,7 +21,7 @@ EXPORTS = (
     "optimus_attn_plan_create", "optimus_attn_plan_update", "optimus_kv_append",
     "optimus_attn_forward", "optimus_attn_plan_destroy", "optimus_attn_plan_num_work_items",
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
-    "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_last_kernel_ms",
+    "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
     "optimus_status_string", "optimus_last_hip_error",
 )
 
@@ -84,7 +84,8 @@ def load_library():
         lib.optimus_attn_plan_get_work_items.restype = i32
         lib.optimus_attn_plan_set_tuning.argtypes = [vp, i32, i32, i32]
         lib.optimus_attn_set_timing.argtypes = [vp, i32]
-        lib.optimus_attn_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        lib.optimus_attn_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float),
+                                                 ctypes.POINTER(ctypes.c_int32)]
         lib.optimus_status_string.argtypes = [ctypes.c_int]
         lib.optimus_status_string.restype = ctypes.c_char_p
         lib.optimus_last_hip_error.argtypes = []
@@ -238,9 +239,11 @@ class Plan:
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_set_timing")
 
-    def last_kernel_ms(self) -> float:
+    def timing_read(self):
+        """(summed attention-kernel milliseconds, forwards recorded) since set_timing(True)."""
         ms = ctypes.c_float(0)
-        rc = self._lib.optimus_attn_last_kernel_ms(self._h, ctypes.byref(ms))
+        n = ctypes.c_int32(0)
+        rc = self._lib.optimus_attn_timing_read(self._h, ctypes.byref(ms), ctypes.byref(n))
         if rc != 0:
-            raise OptimusError(rc, "optimus_attn_last_kernel_ms")
-        return float(ms.value)
+            raise OptimusError(rc, "optimus_attn_timing_read")
+        return float(ms.value), int(n.value)

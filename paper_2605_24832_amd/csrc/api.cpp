@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "plan_internal.h"
 
@@ -38,19 +39,27 @@ struct optimus_attn_plan {
   HostPlan host;
   bool planned = false;
 
-  // device copies of the descriptors and the work list, double-buffered
-  int32_t* dev_buf[2] = {nullptr, nullptr};
-  size_t dev_cap[2] = {0, 0};   // in int32
-  int cur = 0;
-  int32_t* pinned = nullptr;
-  size_t pinned_cap = 0;
-  hipStream_t copy_stream = nullptr;
-  // offsets (int32 units) into dev_buf[cur]
+  // Device copy of the descriptors and the work list.  plan_update fills one
+  // slot of a ring of pinned staging buffers; the first device call after it
+  // enqueues the host-to-device copy on the caller's stream, so the upload is
+  // ordered behind the kernels of earlier iterations that still read the list.
+  static constexpr int kRing = 4;
+  int32_t* staging[kRing] = {nullptr, nullptr, nullptr, nullptr};
+  size_t staging_cap[kRing] = {0, 0, 0, 0};   // in int32
+  hipEvent_t staging_done[kRing] = {nullptr, nullptr, nullptr, nullptr};
+  bool staging_busy[kRing] = {false, false, false, false};
+  int slot = 0;
+  bool dirty = false;          // staging[slot] not yet copied to dev_buf
+  size_t upload_i32 = 0;
+  int32_t* dev_buf = nullptr;
+  size_t dev_cap = 0;          // in int32
+  std::vector<int32_t*> retired;  // outgrown device buffers, freed with the plan
+  // offsets (int32 units) into dev_buf
   size_t off_items = 0, off_merges = 0, off_token_req = 0, off_cu_q = 0, off_prefix = 0, off_bstart = 0;
 
   bool timing = false;
-  bool timed = false;
-  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  std::vector<hipEvent_t> events;  // pairs (start, stop), created on demand
+  size_t events_used = 0;
 };
 
 static int use_device(const optimus_attn_plan* plan) {
@@ -75,7 +84,6 @@ int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
     hipError_t e = hipSetDevice(device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&plan->copy_stream, hipStreamNonBlocking);
     if (e != hipSuccess) {
       set_hip_error((int)e, "plan_create");
       delete plan;
@@ -127,25 +135,33 @@ int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int
   plan->off_bstart = take(hp.block_start.size());
   const size_t total = off;
 
-  if (plan->pinned_cap < total) {
-    if (plan->pinned) OPT_HIP(hipHostFree(plan->pinned), "hipHostFree");
-    plan->pinned = nullptr;
-    plan->pinned_cap = 0;
+  const int sl = (plan->slot + 1) % optimus_attn_plan::kRing;
+  if (plan->staging_busy[sl]) {
+    // the copy out of this slot was enqueued kRing updates ago; wait for it
+    OPT_HIP(hipEventSynchronize(plan->staging_done[sl]), "hipEventSynchronize(staging)");
+    plan->staging_busy[sl] = false;
+  }
+  if (plan->staging_cap[sl] < total) {
+    if (plan->staging[sl]) OPT_HIP(hipHostFree(plan->staging[sl]), "hipHostFree");
+    plan->staging[sl] = nullptr;
+    plan->staging_cap[sl] = 0;
     const size_t cap = total + total / 2 + 1024;
-    OPT_HIP(hipHostMalloc((void**)&plan->pinned, cap * sizeof(int32_t), hipHostMallocDefault),
+    OPT_HIP(hipHostMalloc((void**)&plan->staging[sl], cap * sizeof(int32_t), hipHostMallocDefault),
             "hipHostMalloc");
-    plan->pinned_cap = cap;
+    plan->staging_cap[sl] = cap;
   }
-  const int nb = plan->cur ^ 1;
-  if (plan->dev_cap[nb] < total) {
-    if (plan->dev_buf[nb]) OPT_HIP(hipFree(plan->dev_buf[nb]), "hipFree");
-    plan->dev_buf[nb] = nullptr;
-    plan->dev_cap[nb] = 0;
+  if (!plan->staging_done[sl])
+    OPT_HIP(hipEventCreateWithFlags(&plan->staging_done[sl], hipEventDisableTiming), "hipEventCreate");
+  if (plan->dev_cap < total) {
+    // kernels already enqueued may still read the old buffer: retire it, do not free it now
+    if (plan->dev_buf) plan->retired.push_back(plan->dev_buf);
+    plan->dev_buf = nullptr;
+    plan->dev_cap = 0;
     const size_t cap = total + total / 2 + 1024;
-    OPT_HIP(hipMalloc((void**)&plan->dev_buf[nb], cap * sizeof(int32_t)), "hipMalloc");
-    plan->dev_cap[nb] = cap;
+    OPT_HIP(hipMalloc((void**)&plan->dev_buf, cap * sizeof(int32_t)), "hipMalloc");
+    plan->dev_cap = cap;
   }
-  int32_t* h = plan->pinned;
+  int32_t* h = plan->staging[sl];
   if (!hp.items.empty()) std::memcpy(h + plan->off_items, hp.items.data(), hp.items.size() * 32);
   if (!hp.merges.empty()) std::memcpy(h + plan->off_merges, hp.merges.data(), hp.merges.size() * 32);
   if (!hp.token_req.empty())
@@ -153,12 +169,23 @@ int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int
   std::memcpy(h + plan->off_cu_q, hp.cu_q.data(), hp.cu_q.size() * 4);
   std::memcpy(h + plan->off_prefix, hp.prefix_len.data(), hp.prefix_len.size() * 4);
   std::memcpy(h + plan->off_bstart, hp.block_start.data(), hp.block_start.size() * 4);
-  OPT_HIP(hipMemcpyAsync(plan->dev_buf[nb], h, total * sizeof(int32_t), hipMemcpyHostToDevice,
-                         plan->copy_stream),
-          "hipMemcpyAsync(work list)");
-  OPT_HIP(hipStreamSynchronize(plan->copy_stream), "hipStreamSynchronize(work list)");
-  plan->cur = nb;
+  plan->slot = sl;
+  plan->upload_i32 = total;
+  plan->dirty = true;
   plan->planned = true;
+  return OPTIMUS_OK;
+}
+
+// Enqueue the pending work-list upload (if any) on the caller's stream.
+static int flush_upload(optimus_attn_plan* plan, hipStream_t s) {
+  if (!plan->dirty) return OPTIMUS_OK;
+  const int sl = plan->slot;
+  OPT_HIP(hipMemcpyAsync(plan->dev_buf, plan->staging[sl], plan->upload_i32 * sizeof(int32_t),
+                         hipMemcpyHostToDevice, s),
+          "hipMemcpyAsync(work list)");
+  OPT_HIP(hipEventRecord(plan->staging_done[sl], s), "hipEventRecord(staging)");
+  plan->staging_busy[sl] = true;
+  plan->dirty = false;
   return OPTIMUS_OK;
 }
 
@@ -173,7 +200,9 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
     return OPTIMUS_ERR_INVALID_ARGUMENT;
   int rc = use_device(plan);
   if (rc != OPTIMUS_OK) return rc;
-  const int32_t* d = plan->dev_buf[plan->cur];
+  rc = flush_upload(plan, reinterpret_cast<hipStream_t>(hip_stream));
+  if (rc != OPTIMUS_OK) return rc;
+  const int32_t* d = plan->dev_buf;
   return launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
                           (const uint16_t*)v_new, block_table, d + plan->off_token_req,
                           d + plan->off_cu_q, d + plan->off_prefix, plan->host.total_q, hip_stream);
@@ -195,8 +224,11 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
   int rc = use_device(plan);
   if (rc != OPTIMUS_OK) return rc;
 
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  rc = flush_upload(plan, s);
+  if (rc != OPTIMUS_OK) return rc;
   const optimus_attn_params_t& p = plan->params;
-  const int32_t* d = plan->dev_buf[plan->cur];
+  const int32_t* d = plan->dev_buf;
   KernelArgs a{};
   a.q = (const uint16_t*)q;
   a.k_pool = (const uint16_t*)k_pool;
@@ -220,22 +252,24 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
   const float scale = p.softmax_scale > 0.f ? p.softmax_scale : 1.0f / std::sqrt((float)p.head_dim);
   a.scale_log2 = scale * 1.4426950408889634f;
 
-  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  if (plan->timing) {
-    if (!plan->ev0) {
-      OPT_HIP(hipEventCreate(&plan->ev0), "hipEventCreate");
-      OPT_HIP(hipEventCreate(&plan->ev1), "hipEventCreate");
+  constexpr size_t kMaxTimedForwards = 4096;
+  const bool timed = plan->timing && plan->events_used < 2 * kMaxTimedForwards;
+  if (timed) {
+    while (plan->events.size() < plan->events_used + 2) {
+      hipEvent_t e;
+      OPT_HIP(hipEventCreate(&e), "hipEventCreate");
+      plan->events.push_back(e);
     }
-    OPT_HIP(hipEventRecord(plan->ev0, s), "hipEventRecord");
+    OPT_HIP(hipEventRecord(plan->events[plan->events_used], s), "hipEventRecord");
   }
   for (int nt = 1; nt <= kMaxSubtiles; ++nt) {
     const int32_t first = hp.class_begin[nt - 1], n = hp.class_begin[nt] - first;
     rc = launch_attention(p, a, nt, first, n, hip_stream);
     if (rc != OPTIMUS_OK) return rc;
   }
-  if (plan->timing) {
-    OPT_HIP(hipEventRecord(plan->ev1, s), "hipEventRecord");
-    plan->timed = true;
+  if (timed) {
+    OPT_HIP(hipEventRecord(plan->events[plan->events_used + 1], s), "hipEventRecord");
+    plan->events_used += 2;
   }
   return launch_merge(p, a, (int32_t)hp.merges.size(), hip_stream);
 }
@@ -243,12 +277,14 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
 void optimus_attn_plan_destroy(optimus_attn_plan_t* plan) {
   if (!plan) return;
   if (plan->device >= 0 && hipSetDevice(plan->device) == hipSuccess) {
-    for (int b = 0; b < 2; ++b)
-      if (plan->dev_buf[b]) (void)hipFree(plan->dev_buf[b]);
-    if (plan->pinned) (void)hipHostFree(plan->pinned);
-    if (plan->copy_stream) (void)hipStreamDestroy(plan->copy_stream);
-    if (plan->ev0) (void)hipEventDestroy(plan->ev0);
-    if (plan->ev1) (void)hipEventDestroy(plan->ev1);
+    (void)hipDeviceSynchronize();  // nothing of ours may still read the buffers
+    if (plan->dev_buf) (void)hipFree(plan->dev_buf);
+    for (int32_t* b : plan->retired) (void)hipFree(b);
+    for (int r = 0; r < optimus_attn_plan::kRing; ++r) {
+      if (plan->staging[r]) (void)hipHostFree(plan->staging[r]);
+      if (plan->staging_done[r]) (void)hipEventDestroy(plan->staging_done[r]);
+    }
+    for (hipEvent_t e : plan->events) (void)hipEventDestroy(e);
   }
   delete plan;
 }
@@ -273,18 +309,24 @@ int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable) {
   if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
   plan->timing = enable != 0;
-  if (!plan->timing) plan->timed = false;
+  plan->events_used = 0;
   return OPTIMUS_OK;
 }
 
-int optimus_attn_last_kernel_ms(optimus_attn_plan_t* plan, float* ms_out) {
-  if (!plan || !ms_out) return OPTIMUS_ERR_INVALID_ARGUMENT;
+int optimus_attn_timing_read(optimus_attn_plan_t* plan, float* total_ms_out, int32_t* forwards_out) {
+  if (!plan || !total_ms_out || !forwards_out) return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
-  if (!plan->timed) return OPTIMUS_ERR_NOT_PLANNED;
   int rc = use_device(plan);
   if (rc != OPTIMUS_OK) return rc;
-  OPT_HIP(hipEventSynchronize(plan->ev1), "hipEventSynchronize");
-  OPT_HIP(hipEventElapsedTime(ms_out, plan->ev0, plan->ev1), "hipEventElapsedTime");
+  float total = 0.f;
+  for (size_t i = 0; i + 1 < plan->events_used; i += 2) {
+    float ms = 0.f;
+    OPT_HIP(hipEventSynchronize(plan->events[i + 1]), "hipEventSynchronize");
+    OPT_HIP(hipEventElapsedTime(&ms, plan->events[i], plan->events[i + 1]), "hipEventElapsedTime");
+    total += ms;
+  }
+  *total_ms_out = total;
+  *forwards_out = (int32_t)(plan->events_used / 2);
   return OPTIMUS_OK;
 }
 
