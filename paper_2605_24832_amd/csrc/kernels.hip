@@ -112,45 +112,33 @@ struct SoftmaxState {
   f32x4 acc[NT][D / 16];  // O^T: rows d = 16*db + 4*kg + j, col = query row r16
 };
 
-// One 32-key tile against NT x 16 query rows.
-//   key_base: logical slot of the tile's first key
-//   kv_end:   keys at or beyond are outside the item (only the tail tile)
-//   vis_end:  per lane / subtile, first key the lane's query row may not see
+// One 32-key tile against NT x 16 query rows, operands already in registers.
+//   k[a][s]: A operand of S^T for the a-th group of 16 keys, d step s
+//   v[db]:   A operand of O^T for d block db; its 8 k-slots must be the keys of
+//            this lane's score registers, s0[0..3] then s1[0..3], and the
+//            elements of keys at or beyond kv_end must already be zero
+//   key0/key1: logical slot of the key behind s0[0] / s1[0] of this lane
+//   lim:     per subtile, first key this lane's query row may not see
+//            (only looked at when `masked`)
 template <int D, int NT>
-__device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, KvTile<D>& t,
-                                             const bf16x8 (&qreg)[NT][D / 32], int key_base,
-                                             int kv_end, const int (&vis_end)[NT], bool masked,
-                                             float sc, int kg) {
+__device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, const bf16x8 (&k)[2][D / 32],
+                                             const bf16x8 (&v)[D / 16],
+                                             const bf16x8 (&qreg)[NT][D / 32], int key0, int key1,
+                                             const int (&lim)[NT], bool masked, float sc) {
   constexpr int KS = D / 32, DB = D / 16;
-  if (masked) {
-    // zero V of keys outside the item so that 0 * garbage cannot become NaN
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      const int cnt = kv_end - (key_base + 16 * hf + 4 * kg);  // valid keys among this lane's 4
-      const uint32_t m0 = cnt >= 2 ? 0xffffffffu : (cnt == 1 ? 0x0000ffffu : 0u);
-      const uint32_t m1 = cnt >= 4 ? 0xffffffffu : (cnt == 3 ? 0x0000ffffu : 0u);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        t.v[db][hf].x &= m0;
-        t.v[db][hf].y &= m1;
-      }
-    }
-  }
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][s], qreg[nt][s], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][s], qreg[nt][s], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[0][s], qreg[nt][s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[1][s], qreg[nt][s], s1, 0, 0, 0);
     }
     if (masked) {
-      const int lim = min(kv_end, vis_end[nt]);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int n = key_base + 4 * kg + j;
-        s0[j] = n < lim ? s0[j] : -INFINITY;
-        s1[j] = n + 16 < lim ? s1[j] : -INFINITY;
+        s0[j] = key0 + j < lim[nt] ? s0[j] : -INFINITY;
+        s1[j] = key1 + j < lim[nt] ? s1[j] : -INFINITY;
       }
     }
     float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
@@ -172,13 +160,16 @@ __device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, KvTile<D>&
     for (int j = 0; j < 8; ++j) pt[j] = (__bf16)p[j];
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      f32x4 a = st.acc[nt][db];
-      a *= alpha;
-      u32x4 vv = {t.v[db][0].x, t.v[db][0].y, t.v[db][1].x, t.v[db][1].y};
-      st.acc[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-          __builtin_bit_cast(bf16x8, vv), pt, a, 0, 0, 0);
+      f32x4 acc = st.acc[nt][db];
+      acc *= alpha;
+      st.acc[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[db], pt, acc, 0, 0, 0);
     }
   }
+}
+
+// Keep the first `cnt` of the 2 x bf16 halves (cnt <= 0: none, >= 2: both).
+__device__ __forceinline__ uint32_t keep_mask(int cnt) {
+  return cnt >= 2 ? 0xffffffffu : (cnt == 1 ? 0x0000ffffu : 0u);
 }
 
 template <int D, int LGP, int NT>
@@ -250,7 +241,28 @@ __global__ __launch_bounds__(W * 64, (NT == 1 ? 2 : 1)) void attn_split_wave_ker
   auto COMPUTE = [&](KvTile<D>& t, int i) {
     const int key_base = (t0 + W * i) * kTileTokens;
     const bool masked = key_base + kTileTokens > mask_from;
-    compute_tile<D, NT>(st, t, qreg, key_base, it.kv_end, vis_end, masked, sc, kg);
+    // this lane's score registers: keys 4kg..4kg+3 of each 16-key half
+    const int key0 = key_base + 4 * kg, key1 = key0 + 16;
+    if (masked) {
+      // zero V of keys outside the item so that 0 * garbage cannot become NaN
+      const uint32_t m00 = keep_mask(it.kv_end - key0), m01 = keep_mask(it.kv_end - key0 - 2);
+      const uint32_t m10 = keep_mask(it.kv_end - key1), m11 = keep_mask(it.kv_end - key1 - 2);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        t.v[db][0].x &= m00; t.v[db][0].y &= m01;
+        t.v[db][1].x &= m10; t.v[db][1].y &= m11;
+      }
+    }
+    bf16x8 vop[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      u32x4 vv = {t.v[db][0].x, t.v[db][0].y, t.v[db][1].x, t.v[db][1].y};
+      vop[db] = __builtin_bit_cast(bf16x8, vv);
+    }
+    int lim[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) lim[nt] = min(it.kv_end, vis_end[nt]);
+    compute_tile<D, NT>(st, t.k, vop, qreg, key0, key1, lim, masked, sc);
   };
   if (n > 0) {
     LOAD(ta, 0);
@@ -359,6 +371,221 @@ __global__ __launch_bounds__(W * 64, (NT == 1 ? 2 : 1)) void attn_split_wave_ker
   }
 }
 
+// attention kernel for wide row tiles ("lds-tile"): up to 64*NT query rows per
+// work item.  All 4 waves walk the same 32-key tiles, staged once per workgroup
+// in LDS (coalesced global loads -> registers -> ds_write, double-buffered, two
+// tiles of loads in flight), and each wave owns NT x 16 of the rows, so K/V
+// leave HBM once however many query heads and chunk tokens share them.
+// LDS layouts are chosen so that every operand read is a conflict-free
+// ds_read_b128:
+//   K: [d group of 8][position][8] with the 32 keys in MFMA row order: key
+//      8x+4a+y (x 0..3, a 0..1, y 0..3) at position 16a+4x+y, so that the two
+//      S^T products of a lane yield keys 8kg..8kg+7, the k-slots of one
+//      16-byte V^T operand;
+//   V: [key octet 0..3][d][8 keys].
+template <int D, int LGP, int NT>
+__global__ __launch_bounds__(256, (NT <= 2 ? 2 : 1)) void attn_lds_tile_kernel(KernelArgs a, int first_item) {
+  constexpr int KS = D / 32, DB = D / 16, P = 1 << LGP;
+  constexpr int PIECES = D * 4;        // 16-byte pieces of a K (= of a V) tile
+  constexpr int LPT = PIECES / 256;    // pieces per thread per tensor per tile
+  __shared__ u32x4 sm_k[2][PIECES];
+  __shared__ u32x4 sm_v[2][PIECES];
+
+  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int G = a.group;
+
+  bf16x8 qreg[NT][KS];
+  int vis_end[NT];
+  const int L = a.prefix_len[it.req];
+  const int d_in = L - a.block_start[it.req];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int rl = (wave * NT + nt) * 16 + r16;
+    const bool valid = rl < it.row_count;
+    const int row = it.row_begin + (valid ? rl : 0);
+    const int j = row / G, u = row - j * G;
+    const uint16_t* qp =
+        a.q + ((int64_t)(it.q_token0 + j) * a.num_q_heads + it.kv_head * G + u) * D + kg * 8;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      u32x4 x = *reinterpret_cast<const u32x4*>(qp + s * 32);
+      if (!valid) x = u32x4{0u, 0u, 0u, 0u};
+      qreg[nt][s] = __builtin_bit_cast(bf16x8, x);
+    }
+    vis_end[nt] = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + j) / a.block_size + 1) * a.block_size - d_in;
+  }
+  const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
+  const int mask_from = min(it.kv_end, vis_min);
+  const bool wave_has_rows = wave * NT * 16 < it.row_count;  // uniform per wave
+
+  SoftmaxState<D, NT> st;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    st.m[nt] = -INFINITY;
+    st.l[nt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) st.acc[nt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int32_t* bt = a.block_table + (int64_t)it.req * a.max_pages_per_req;
+  const int last_page = (it.kv_end - 1) >> LGP;
+  const char* kbase = reinterpret_cast<const char*>(a.k_pool + (int64_t)it.kv_head * a.k_stride_head);
+  const char* vbase = reinterpret_cast<const char*>(a.v_pool + (int64_t)it.kv_head * a.v_stride_head);
+  const int64_t kspb = a.k_stride_page * 2, vspb = a.v_stride_page * 2;
+  const float sc = a.scale_log2;
+  const int tile_lo = it.kv_begin / kTileTokens;
+  const int n = (it.kv_end + kTileTokens - 1) / kTileTokens - tile_lo;
+
+  // per-thread piece geometry (tile invariant)
+  uint32_t ksrc[LPT], vsrc[LPT];   // byte offset inside the page (P = 16) or before slot0 is added
+  int kdst[LPT], vdst[LPT];        // piece index in the LDS tile
+  bool second_page[LPT][2];        // P = 16: piece comes from the tile's second page (K, V)
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    const int e = tid + 256 * i;
+    const int chunk = e >> 5, kit = e & 31;
+    kdst[i] = chunk * 32 + (((kit >> 2) & 1) << 4) + ((kit >> 3) << 2) + (kit & 3);
+    const int dd = e >> 2, q4 = e & 3;
+    vdst[i] = q4 * D + dd;
+    if constexpr (LGP == 4) {
+      ksrc[i] = (uint32_t)(chunk * 16 + (kit & 15)) * 16u;
+      vsrc[i] = (uint32_t)(dd * 32 + (q4 & 1) * 16);
+      second_page[i][0] = kit >= 16;
+      second_page[i][1] = q4 >= 2;
+    } else {
+      ksrc[i] = (uint32_t)(chunk * P + kit) * 16u;
+      vsrc[i] = (uint32_t)(dd * P + 8 * q4) * 2u;
+      second_page[i][0] = second_page[i][1] = false;
+    }
+  }
+
+  u32x4 rk[2][LPT], rv[2][LPT];
+  auto LOAD = [&](int set, int t) {   // tile t of the item -> registers
+    const int tile = tile_lo + t;
+    if constexpr (LGP == 4) {
+      const int pi0 = tile * 2, pi1 = min(pi0 + 1, last_page);
+      const int64_t pg0 = bt[pi0], pg1 = bt[pi1];
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) {
+        const char* kp = kbase + (second_page[i][0] ? pg1 : pg0) * kspb;
+        const char* vp = vbase + (second_page[i][1] ? pg1 : pg0) * vspb;
+        rk[set][i] = *reinterpret_cast<const u32x4*>(kp + ksrc[i]);
+        rv[set][i] = *reinterpret_cast<const u32x4*>(vp + vsrc[i]);
+      }
+    } else {
+      const int64_t pg = bt[(tile * kTileTokens) >> LGP];
+      const uint32_t slot0 = (uint32_t)((tile * kTileTokens) & (P - 1));
+      const char* kp = kbase + pg * kspb + slot0 * 16u;
+      const char* vp = vbase + pg * vspb + slot0 * 2u;
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) {
+        rk[set][i] = *reinterpret_cast<const u32x4*>(kp + ksrc[i]);
+        rv[set][i] = *reinterpret_cast<const u32x4*>(vp + vsrc[i]);
+      }
+    }
+  };
+  auto STORE = [&](int buf, int set) {  // registers -> LDS tile
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      sm_k[buf][kdst[i]] = rk[set][i];
+      sm_v[buf][vdst[i]] = rv[set][i];
+    }
+  };
+  auto COMPUTE = [&](int buf, int t) {
+    if (!wave_has_rows) return;
+    const int key_base = (tile_lo + t) * kTileTokens;
+    const bool masked = key_base + kTileTokens > mask_from;
+    const int key0 = key_base + 8 * kg, key1 = key0 + 4;
+    bf16x8 kop[2][KS], vop[DB];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kop[0][s] = __builtin_bit_cast(bf16x8, sm_k[buf][(4 * s + kg) * 32 + r16]);
+      kop[1][s] = __builtin_bit_cast(bf16x8, sm_k[buf][(4 * s + kg) * 32 + 16 + r16]);
+    }
+    if (masked) {
+      const int cnt = it.kv_end - key0;
+      const uint32_t m0 = keep_mask(cnt), m1 = keep_mask(cnt - 2), m2 = keep_mask(cnt - 4),
+                     m3 = keep_mask(cnt - 6);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u32x4 vv = sm_v[buf][kg * D + 16 * db + r16];
+        vv.x &= m0; vv.y &= m1; vv.z &= m2; vv.w &= m3;
+        vop[db] = __builtin_bit_cast(bf16x8, vv);
+      }
+    } else {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        vop[db] = __builtin_bit_cast(bf16x8, sm_v[buf][kg * D + 16 * db + r16]);
+    }
+    int lim[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) lim[nt] = min(it.kv_end, vis_end[nt]);
+    compute_tile<D, NT>(st, kop, vop, qreg, key0, key1, lim, masked, sc);
+  };
+
+  // invariant at the top of iteration t: LDS buffer t%2 holds tile t; register
+  // set (t+1)%2 holds tile t+1 and set t%2 holds tile t+2 (loads in flight).
+  LOAD(0, 0);
+  if (n > 1) LOAD(1, 1);
+  STORE(0, 0);
+  if (n > 2) LOAD(0, 2);
+  __syncthreads();
+  for (int t = 0; t < n; t += 2) {
+    COMPUTE(0, t);
+    if (t + 1 < n) STORE(1, 1);
+    if (t + 3 < n) LOAD(1, t + 3);
+    __syncthreads();
+    if (t + 1 >= n) break;
+    COMPUTE(1, t + 1);
+    if (t + 2 < n) STORE(0, 0);
+    if (t + 4 < n) LOAD(0, t + 4);
+    __syncthreads();
+  }
+
+  // ---- each wave owns its rows: finish them without any cross-wave step ----
+  if (!wave_has_rows) return;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int rl = (wave * NT + nt) * 16 + r16;
+    const float lsum = xor_sum(st.l[nt]);
+    if (rl >= it.row_count) continue;
+    if (it.part_row >= 0) {
+      float* po = a.ws_o + (int64_t)(it.part_row + rl) * D + 4 * kg;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db) = st.acc[nt][db];
+      if (kg == 0) {
+        float* pml = a.ws_ml + (int64_t)(it.part_row + rl) * 2;
+        pml[0] = st.m[nt];
+        pml[1] = lsum;
+      }
+    } else {
+      const float inv = 1.f / lsum;
+      const int row = it.row_begin + rl;
+      const int j = row / G, u = row - j * G;
+      const int64_t off =
+          ((int64_t)(it.q_token0 + j) * a.num_q_heads + it.kv_head * G + u) * D + 4 * kg;
+      if (a.out_fp32) {
+        float* po = reinterpret_cast<float*>(a.out) + off;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db) = st.acc[nt][db] * inv;
+      } else {
+        __bf16* po = reinterpret_cast<__bf16*>(a.out) + off;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          bf16x4 b;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) b[e] = (__bf16)(st.acc[nt][db][e] * inv);
+          *reinterpret_cast<bf16x4*>(po + 16 * db) = b;
+        }
+      }
+    }
+  }
+}
+
 // Merge of split-KV partials: for each row, M = max_s m_s,
 //   o = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
 // Block (256 threads) = (merge item, group of 16 rows); thread = (row, D/16 columns).
@@ -441,38 +668,40 @@ __global__ __launch_bounds__(D) void kv_append_kernel(
 // ------------------------------------------------------------------ launchers
 
 template <int D, int LGP>
-static int launch_attention_dp(const KernelArgs& a, int subtiles, int32_t first_item, int32_t n_items,
+static int launch_attention_dp(const KernelArgs& a, int cls, int32_t first_item, int32_t n_items,
                                hipStream_t stream) {
   const dim3 grid(n_items), block(W * 64);
-  switch (subtiles) {
-    case 1: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 1>), grid, block, 0, stream, a, first_item); break;
-    case 2: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 2>), grid, block, 0, stream, a, first_item); break;
-    case 3: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 3>), grid, block, 0, stream, a, first_item); break;
-    case 4: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 4>), grid, block, 0, stream, a, first_item); break;
+  switch (cls) {
+    case 0: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 1>), grid, block, 0, stream, a, first_item); break;
+    case 1: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 2>), grid, block, 0, stream, a, first_item); break;
+    case 2: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 1>), grid, block, 0, stream, a, first_item); break;
+    case 3: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 2>), grid, block, 0, stream, a, first_item); break;
+    case 4: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 3>), grid, block, 0, stream, a, first_item); break;
+    case 5: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 4>), grid, block, 0, stream, a, first_item); break;
     default: return OPTIMUS_ERR_INVALID_ARGUMENT;
   }
   return OPTIMUS_OK;
 }
 
 template <int D>
-static int launch_attention_d(const optimus_attn_params_t& p, const KernelArgs& a, int subtiles,
+static int launch_attention_d(const optimus_attn_params_t& p, const KernelArgs& a, int cls,
                               int32_t first_item, int32_t n_items, hipStream_t stream) {
   switch (p.page_size) {
-    case 16: return launch_attention_dp<D, 4>(a, subtiles, first_item, n_items, stream);
-    case 32: return launch_attention_dp<D, 5>(a, subtiles, first_item, n_items, stream);
-    case 64: return launch_attention_dp<D, 6>(a, subtiles, first_item, n_items, stream);
-    case 128: return launch_attention_dp<D, 7>(a, subtiles, first_item, n_items, stream);
+    case 16: return launch_attention_dp<D, 4>(a, cls, first_item, n_items, stream);
+    case 32: return launch_attention_dp<D, 5>(a, cls, first_item, n_items, stream);
+    case 64: return launch_attention_dp<D, 6>(a, cls, first_item, n_items, stream);
+    case 128: return launch_attention_dp<D, 7>(a, cls, first_item, n_items, stream);
     default: return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
   }
 }
 
-int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int subtiles,
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int cls,
                      int32_t first_item, int32_t n_items, void* stream) {
   if (n_items <= 0) return OPTIMUS_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int rc;
-  if (p.head_dim == 128) rc = launch_attention_d<128>(p, a, subtiles, first_item, n_items, s);
-  else if (p.head_dim == 64) rc = launch_attention_d<64>(p, a, subtiles, first_item, n_items, s);
+  if (p.head_dim == 128) rc = launch_attention_d<128>(p, a, cls, first_item, n_items, s);
+  else if (p.head_dim == 64) rc = launch_attention_d<64>(p, a, cls, first_item, n_items, s);
   else return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
   if (rc != OPTIMUS_OK) return rc;
   hipError_t e = hipGetLastError();
@@ -483,7 +712,7 @@ int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int su
 int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges, void* stream) {
   if (n_merges <= 0) return OPTIMUS_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  const dim3 grid(n_merges, kMaxSubtiles), block(256);
+  const dim3 grid(n_merges, kMaxRowsPerItem / kRowsPerSubtile), block(256);
   if (p.head_dim == 128) hipLaunchKernelGGL((merge_kernel<128>), grid, block, 0, s, a);
   else hipLaunchKernelGGL((merge_kernel<64>), grid, block, 0, s, a);
   hipError_t e = hipGetLastError();

@@ -12,8 +12,17 @@ namespace optimus {
 
 constexpr int kTileTokens = 32;     // keys per MFMA tile step (one 16x16x32 PV contraction)
 constexpr int kRowsPerSubtile = 16; // query rows per MFMA N tile
-constexpr int kMaxSubtiles = 4;     // a work item holds at most 4 x 16 = 64 query rows
 constexpr int kWavesPerBlock = 4;
+// Kernel classes.  0..1: split-wave kernel with 1..2 subtiles per wave (<= 32 rows, the
+// waves split the keys).  2..5: lds-tile kernel with 1..4 subtiles per wave (<= 64..256
+// rows, the waves split the rows).
+constexpr int kNumClasses = 6;
+constexpr int kSplitWaveMaxRows = 32;
+constexpr int kMaxRowsPerItem = 256;
+inline int class_of_rows(int rows) {
+  if (rows <= kSplitWaveMaxRows) return (rows + kRowsPerSubtile - 1) / kRowsPerSubtile - 1;
+  return 2 + (rows + 4 * kRowsPerSubtile - 1) / (4 * kRowsPerSubtile) - 1;
+}
 
 // One merge job: `n_splits` partials of the same q tile, stored back to back
 // (`row_count` rows each) starting at workspace row `first_part_row`.
@@ -37,8 +46,8 @@ struct Tuning {
 struct HostPlan {
   int32_t batch = 0;
   int32_t total_q = 0;
-  std::vector<optimus_work_item_t> items;  // sorted by subtile class, then cost
-  int32_t class_begin[kMaxSubtiles + 1] = {0, 0, 0, 0, 0};  // items of class nt: [class_begin[nt-1], class_begin[nt])
+  std::vector<optimus_work_item_t> items;  // sorted by kernel class, then cost
+  int32_t class_begin[kNumClasses + 1] = {0, 0, 0, 0, 0, 0, 0};  // items of class c: [class_begin[c], class_begin[c+1])
   std::vector<MergeItem> merges;
   std::vector<int32_t> token_req;   // [T] request of each query token
   std::vector<int32_t> cu_q, prefix_len, block_start;
@@ -74,7 +83,7 @@ struct KernelArgs {
 };
 
 // Kernel launchers (kernels.hip).  `stream` is a hipStream_t.
-int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int subtiles,
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int kernel_class,
                      int32_t first_item, int32_t n_items, void* stream);
 int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges,
                  void* stream);

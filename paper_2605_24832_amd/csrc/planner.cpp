@@ -74,24 +74,28 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     for (int t = cu_q[i]; t < cu_q[i + 1]; ++t) hp.token_req[t] = i;
 
   // ---- how many keys one work item scans ----
-  const int max_rows = kRowsPerSubtile * kMaxSubtiles;
-  int64_t total_units = 0;  // (q tile, kv head, 32-key tile) units over the batch
+  // Relative cost of one 32-key tile per kernel class (measured, rounded): the split-wave
+  // classes are bound by the K/V stream, the wide lds-tile classes by MFMA + softmax work.
+  static const double kClassCost[kNumClasses] = {1.0, 1.3, 1.3, 2.0, 3.0, 4.0};
+  double total_cost = 0.0;
   for (int i = 0; i < batch; ++i) {
     const int64_t c = cu_q[i + 1] - cu_q[i];
     if (c == 0) continue;
-    const int64_t rows = c * G, n_qt = ceil_div(rows, max_rows);
-    total_units += n_qt * Hkv * ceil_div((int64_t)prefix_len[i] + c, kTileTokens);
+    const int64_t rows = c * G;
+    const int64_t tiles = ceil_div((int64_t)prefix_len[i] + c, kTileTokens);
+    for (int64_t r0 = 0; r0 < rows; r0 += kMaxRowsPerItem)
+      total_cost += (double)Hkv * tiles *
+                    kClassCost[class_of_rows((int)std::min<int64_t>(kMaxRowsPerItem, rows - r0))];
   }
-  const int64_t target_items = tuning.target_items > 0 ? tuning.target_items : 16 * (int64_t)num_cus;
+  const int64_t target_items = tuning.target_items > 0 ? tuning.target_items : 4 * (int64_t)num_cus;
   const int64_t min_tiles =
       std::max<int64_t>(1, (tuning.min_split_tokens > 0 ? tuning.min_split_tokens : 256) / kTileTokens);
   const int64_t max_tiles = std::max<int64_t>(
       min_tiles, (tuning.max_split_tokens > 0 ? tuning.max_split_tokens : 8192) / kTileTokens);
-  const int64_t tiles_per_item =
-      std::min(max_tiles, std::max(min_tiles, ceil_div(total_units, std::max<int64_t>(target_items, 1))));
+  const double target_cost = total_cost / (double)std::max<int64_t>(target_items, 1);
 
   // ---- emit items ----
-  struct Keyed { optimus_work_item_t it; int nt; int64_t cost; };
+  struct Keyed { optimus_work_item_t it; int cls; double cost; };
   std::vector<Keyed> keyed;
   int64_t part_rows = 0;
   for (int i = 0; i < batch; ++i) {
@@ -100,12 +104,14 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     const int kv_len = prefix_len[i] + c;
     const int rows = c * G;
     const int n_tiles = (int)ceil_div(kv_len, kTileTokens);
-    const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
-    const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
     for (int g = 0; g < Hkv; ++g) {
-      for (int r0 = 0; r0 < rows; r0 += max_rows) {
-        const int rc = std::min(max_rows, rows - r0);
-        const int nt_raw = (int)ceil_div(rc, kRowsPerSubtile);
+      for (int r0 = 0; r0 < rows; r0 += kMaxRowsPerItem) {
+        const int rc = std::min(kMaxRowsPerItem, rows - r0);
+        const int cls = class_of_rows(rc);
+        const int64_t tiles_per_item = std::min(
+            max_tiles, std::max(min_tiles, (int64_t)std::ceil(target_cost / kClassCost[cls])));
+        const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
+        const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
         int32_t first_part = -1;
         if (n_splits > 1) {
           first_part = (int32_t)part_rows;
@@ -121,32 +127,32 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
           it.kv_begin = s * tiles_per_split * kTileTokens;
           it.kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
           if (it.kv_begin >= it.kv_end) {
-            // cannot happen: n_splits = ceil(n_tiles / tiles_per_item) and
-            // tiles_per_split = ceil(n_tiles / n_splits) leave no empty split
+            // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
+            // cover all n_tiles
             return OPTIMUS_ERR_INVALID_ARGUMENT;
           }
           it.part_row = n_splits > 1 ? first_part + s * rc : -1;
           it.q_token0 = cu_q[i];
           const int64_t tiles = ceil_div(it.kv_end - it.kv_begin, kTileTokens);
-          keyed.push_back({it, nt_raw, tiles * (2 + nt_raw)});
+          keyed.push_back({it, cls, tiles * kClassCost[cls]});
         }
       }
     }
   }
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  // class = number of 16-row subtiles the kernel variant carries; heavy items first
+  // grouped by kernel class (one launch each); heavy items first inside a class
   std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
-    if (a.nt != b.nt) return a.nt < b.nt;
+    if (a.cls != b.cls) return a.cls < b.cls;
     return a.cost > b.cost;
   });
   hp.items.reserve(keyed.size());
-  for (int nt = 0; nt <= kMaxSubtiles; ++nt) hp.class_begin[nt] = 0;
+  int32_t count[kNumClasses] = {0, 0, 0, 0, 0, 0};
   for (const Keyed& k : keyed) {
     hp.items.push_back(k.it);
-    hp.class_begin[k.nt] = (int32_t)hp.items.size();
+    ++count[k.cls];
   }
-  for (int nt = 1; nt <= kMaxSubtiles; ++nt)
-    hp.class_begin[nt] = std::max(hp.class_begin[nt], hp.class_begin[nt - 1]);
+  hp.class_begin[0] = 0;
+  for (int c = 0; c < kNumClasses; ++c) hp.class_begin[c + 1] = hp.class_begin[c] + count[c];
   hp.part_rows = part_rows;
   hp.workspace_bytes = (size_t)part_rows * (size_t)(p.head_dim + 2) * sizeof(float);
   return OPTIMUS_OK;

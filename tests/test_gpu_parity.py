@@ -95,6 +95,26 @@ def test_gqa7_many_q_tiles(oracle_mod):
     full_parity(oracle_mod, w, "gqa7")
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,P", [(12, 2, 128, 16), (32, 2, 64, 32), (16, 1, 128, 64)])
+def test_wide_row_tiles(oracle_mod, Hq, Hkv, D, P):
+    """Every lds-tile class: 33..64, 65..128, 129..192, 193..256 rows and more than 256 rows
+    (several row tiles), unsplit and split, with ragged key tails."""
+    _say(f"wide rows Hq={Hq} Hkv={Hkv} D={D} P={P}")
+    G = Hq // Hkv
+    chunks = sorted({-(-r // G) for r in (33, 64, 65, 128, 129, 192, 193, 256, 257, 300, 512)} - {0})
+    chunks = [c for c in chunks if c <= 64]
+    L = [37 + 61 * k for k in range(len(chunks))]
+    w = inputs.make_workload("wide", seed=41 + Hq, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D,
+                             page_size=P, block_size=64, prefix_len=L, chunk=chunks,
+                             block_inner=[0] * len(L), device=DEV)
+    full_parity(oracle_mod, w, "wide rows")
+    w2 = inputs.make_workload("wide", seed=41 + Hq, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D,
+                              page_size=P, block_size=64, prefix_len=L, chunk=chunks,
+                              block_inner=[0] * len(L), device=DEV)
+    full_parity(oracle_mod, w2, "wide rows split",
+                tuning=dict(target_items=1 << 20, min_split_tokens=64, max_split_tokens=64))
+
+
 def test_forced_splits_and_merge(oracle_mod):
     """Tiny split size: many partials per row, including splits some waves get no tile of."""
     _say("forced splits")
