@@ -262,10 +262,10 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
     }
     OPT_HIP(hipEventRecord(plan->events[plan->events_used], s), "hipEventRecord");
   }
-  // the widest (longest-running) class first
-  for (int c = kNumClasses - 1; c >= 0; --c) {
-    const int32_t first = hp.class_begin[c], n = hp.class_begin[c + 1] - first;
-    rc = launch_attention(p, a, c, first, n, hip_stream);
+  // the heavy group (long-running items) first
+  for (int g = kNumGroups - 1; g >= 0; --g) {
+    const int32_t first = hp.group_begin[g], n = hp.group_begin[g + 1] - first;
+    rc = launch_attention(p, a, g, first, n, hip_stream);
     if (rc != OPTIMUS_OK) return rc;
   }
   if (timed) {

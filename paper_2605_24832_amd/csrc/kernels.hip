@@ -172,15 +172,19 @@ __device__ __forceinline__ uint32_t keep_mask(int cnt) {
   return cnt >= 2 ? 0xffffffffu : (cnt == 1 ? 0x0000ffffu : 0u);
 }
 
+// Shared memory of the split-wave body, in floats.
+template <int D, int NT>
+constexpr int split_wave_smem_floats() { return W * 16 * (D + 4) + 2 * W * NT * 16; }
+
 template <int D, int LGP, int NT>
-__global__ __launch_bounds__(W * 64, (NT == 1 ? 2 : 1)) void attn_split_wave_kernel(KernelArgs a, int first_item) {
+__device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optimus_work_item_t& it,
+                                                float* smem) {
   constexpr int KS = D / 32, DB = D / 16;
   constexpr int OPAD = D + 4;
-  __shared__ float sm_o[W][16][OPAD];
-  __shared__ float sm_m[W][NT * 16];
-  __shared__ float sm_l[W][NT * 16];
+  float (*sm_o)[16][OPAD] = reinterpret_cast<float (*)[16][OPAD]>(smem);
+  float (*sm_m)[NT * 16] = reinterpret_cast<float (*)[NT * 16]>(smem + W * 16 * OPAD);
+  float (*sm_l)[NT * 16] = reinterpret_cast<float (*)[NT * 16]>(smem + W * 16 * OPAD + W * NT * 16);
 
-  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r16 = lane & 15, kg = lane >> 4;
@@ -383,15 +387,18 @@ __global__ __launch_bounds__(W * 64, (NT == 1 ? 2 : 1)) void attn_split_wave_ker
 //      S^T products of a lane yield keys 8kg..8kg+7, the k-slots of one
 //      16-byte V^T operand;
 //   V: [key octet 0..3][d][8 keys].
+template <int D>
+constexpr int lds_tile_smem_floats() { return 4 * (D * 4) * 4; }  // 2 x (K + V) tiles of D*4 x 16 bytes
+
 template <int D, int LGP, int NT>
-__global__ __launch_bounds__(256, (NT <= 2 ? 2 : 1)) void attn_lds_tile_kernel(KernelArgs a, int first_item) {
+__device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus_work_item_t& it,
+                                              float* smem) {
   constexpr int KS = D / 32, DB = D / 16, P = 1 << LGP;
   constexpr int PIECES = D * 4;        // 16-byte pieces of a K (= of a V) tile
   constexpr int LPT = PIECES / 256;    // pieces per thread per tensor per tile
-  __shared__ u32x4 sm_k[2][PIECES];
-  __shared__ u32x4 sm_v[2][PIECES];
+  u32x4 (*sm_k)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem);
+  u32x4 (*sm_v)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem + 2 * PIECES * 4);
 
-  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -586,6 +593,30 @@ __global__ __launch_bounds__(256, (NT <= 2 ? 2 : 1)) void attn_lds_tile_kernel(K
   }
 }
 
+// One launch serves several kernel classes: the block looks at its item's row
+// count and runs the matching body, so that a ragged batch (chunk sizes 1..32
+// side by side) is one grid in longest-first order instead of one small grid
+// per class.  Two launch groups because of registers: the light group (<= 128
+// rows per item) fits 2 waves per SIMD, the heavy group (<= 256 rows) fits 1.
+template <int D, int LGP>
+__global__ __launch_bounds__(W * 64, 2) void attn_light_kernel(KernelArgs a, int first_item) {
+  constexpr int kFloats = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
+                              ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
+  __shared__ __attribute__((aligned(16))) float smem[kFloats];
+  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
+  if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
+  else if (it.row_count <= 64) lds_tile_body<D, LGP, 1>(a, it, smem);
+  else lds_tile_body<D, LGP, 2>(a, it, smem);
+}
+
+template <int D, int LGP>
+__global__ __launch_bounds__(W * 64, 1) void attn_heavy_kernel(KernelArgs a, int first_item) {
+  __shared__ __attribute__((aligned(16))) float smem[lds_tile_smem_floats<D>()];
+  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
+  if (it.row_count <= 192) lds_tile_body<D, LGP, 3>(a, it, smem);
+  else lds_tile_body<D, LGP, 4>(a, it, smem);
+}
+
 // Merge of split-KV partials: for each row, M = max_s m_s,
 //   o = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
 // Block (256 threads) = (merge item, group of 16 rows); thread = (row, D/16 columns).
@@ -668,18 +699,12 @@ __global__ __launch_bounds__(D) void kv_append_kernel(
 // ------------------------------------------------------------------ launchers
 
 template <int D, int LGP>
-static int launch_attention_dp(const KernelArgs& a, int cls, int32_t first_item, int32_t n_items,
+static int launch_attention_dp(const KernelArgs& a, int group, int32_t first_item, int32_t n_items,
                                hipStream_t stream) {
   const dim3 grid(n_items), block(W * 64);
-  switch (cls) {
-    case 0: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 1>), grid, block, 0, stream, a, first_item); break;
-    case 1: hipLaunchKernelGGL((attn_split_wave_kernel<D, LGP, 2>), grid, block, 0, stream, a, first_item); break;
-    case 2: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 1>), grid, block, 0, stream, a, first_item); break;
-    case 3: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 2>), grid, block, 0, stream, a, first_item); break;
-    case 4: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 3>), grid, block, 0, stream, a, first_item); break;
-    case 5: hipLaunchKernelGGL((attn_lds_tile_kernel<D, LGP, 4>), grid, block, 0, stream, a, first_item); break;
-    default: return OPTIMUS_ERR_INVALID_ARGUMENT;
-  }
+  if (group == 0) hipLaunchKernelGGL((attn_light_kernel<D, LGP>), grid, block, 0, stream, a, first_item);
+  else if (group == 1) hipLaunchKernelGGL((attn_heavy_kernel<D, LGP>), grid, block, 0, stream, a, first_item);
+  else return OPTIMUS_ERR_INVALID_ARGUMENT;
   return OPTIMUS_OK;
 }
 

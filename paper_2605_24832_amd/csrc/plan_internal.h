@@ -13,15 +13,19 @@ namespace optimus {
 constexpr int kTileTokens = 32;     // keys per MFMA tile step (one 16x16x32 PV contraction)
 constexpr int kRowsPerSubtile = 16; // query rows per MFMA N tile
 constexpr int kWavesPerBlock = 4;
-// Kernel classes.  0..1: split-wave kernel with 1..2 subtiles per wave (<= 32 rows, the
-// waves split the keys).  2..5: lds-tile kernel with 1..4 subtiles per wave (<= 64..256
-// rows, the waves split the rows).
-constexpr int kNumClasses = 6;
-constexpr int kSplitWaveMaxRows = 32;
+// Launch groups.  0 "light": items of <= 128 query rows (<= 16 rows: the split-wave
+// body, the waves split the keys; 17..128 rows: the lds-tile body with 1..2 subtiles per
+// wave, the waves split the rows); 1 "heavy": 129..256 rows (lds-tile body, 3..4 subtiles).
+constexpr int kNumGroups = 2;
+constexpr int kLightMaxRows = 128;
 constexpr int kMaxRowsPerItem = 256;
-inline int class_of_rows(int rows) {
-  if (rows <= kSplitWaveMaxRows) return (rows + kRowsPerSubtile - 1) / kRowsPerSubtile - 1;
-  return 2 + (rows + 4 * kRowsPerSubtile - 1) / (4 * kRowsPerSubtile) - 1;
+inline int group_of_rows(int rows) { return rows <= kLightMaxRows ? 0 : 1; }
+// Relative cost of one 32-key tile for an item of `rows` query rows: the narrow items are
+// bound by the K/V stream, the wide ones by MFMA + softmax work.
+inline double tile_cost_of_rows(int rows) {
+  if (rows <= 16) return 1.0;
+  if (rows <= 64) return 1.3;
+  return (double)((rows + 63) / 64);
 }
 
 // One merge job: `n_splits` partials of the same q tile, stored back to back
@@ -46,8 +50,8 @@ struct Tuning {
 struct HostPlan {
   int32_t batch = 0;
   int32_t total_q = 0;
-  std::vector<optimus_work_item_t> items;  // sorted by kernel class, then cost
-  int32_t class_begin[kNumClasses + 1] = {0, 0, 0, 0, 0, 0, 0};  // items of class c: [class_begin[c], class_begin[c+1])
+  std::vector<optimus_work_item_t> items;  // sorted by launch group, then cost (heaviest first)
+  int32_t group_begin[kNumGroups + 1] = {0, 0, 0};  // items of group g: [group_begin[g], group_begin[g+1])
   std::vector<MergeItem> merges;
   std::vector<int32_t> token_req;   // [T] request of each query token
   std::vector<int32_t> cu_q, prefix_len, block_start;
@@ -83,7 +87,7 @@ struct KernelArgs {
 };
 
 // Kernel launchers (kernels.hip).  `stream` is a hipStream_t.
-int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int kernel_class,
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int launch_group,
                      int32_t first_item, int32_t n_items, void* stream);
 int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges,
                  void* stream);

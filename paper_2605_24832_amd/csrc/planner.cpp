@@ -74,9 +74,6 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     for (int t = cu_q[i]; t < cu_q[i + 1]; ++t) hp.token_req[t] = i;
 
   // ---- how many keys one work item scans ----
-  // Relative cost of one 32-key tile per kernel class (measured, rounded): the split-wave
-  // classes are bound by the K/V stream, the wide lds-tile classes by MFMA + softmax work.
-  static const double kClassCost[kNumClasses] = {1.0, 1.3, 1.3, 2.0, 3.0, 4.0};
   double total_cost = 0.0;
   for (int i = 0; i < batch; ++i) {
     const int64_t c = cu_q[i + 1] - cu_q[i];
@@ -85,7 +82,7 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     const int64_t tiles = ceil_div((int64_t)prefix_len[i] + c, kTileTokens);
     for (int64_t r0 = 0; r0 < rows; r0 += kMaxRowsPerItem)
       total_cost += (double)Hkv * tiles *
-                    kClassCost[class_of_rows((int)std::min<int64_t>(kMaxRowsPerItem, rows - r0))];
+                    tile_cost_of_rows((int)std::min<int64_t>(kMaxRowsPerItem, rows - r0));
   }
   const int64_t target_items = tuning.target_items > 0 ? tuning.target_items : 4 * (int64_t)num_cus;
   const int64_t min_tiles =
@@ -95,7 +92,7 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   const double target_cost = total_cost / (double)std::max<int64_t>(target_items, 1);
 
   // ---- emit items ----
-  struct Keyed { optimus_work_item_t it; int cls; double cost; };
+  struct Keyed { optimus_work_item_t it; int group; double cost; };
   std::vector<Keyed> keyed;
   int64_t part_rows = 0;
   for (int i = 0; i < batch; ++i) {
@@ -107,9 +104,9 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     for (int g = 0; g < Hkv; ++g) {
       for (int r0 = 0; r0 < rows; r0 += kMaxRowsPerItem) {
         const int rc = std::min(kMaxRowsPerItem, rows - r0);
-        const int cls = class_of_rows(rc);
+        const double tile_cost = tile_cost_of_rows(rc);
         const int64_t tiles_per_item = std::min(
-            max_tiles, std::max(min_tiles, (int64_t)std::ceil(target_cost / kClassCost[cls])));
+            max_tiles, std::max(min_tiles, (int64_t)std::ceil(target_cost / tile_cost)));
         const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
         const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
         int32_t first_part = -1;
@@ -134,25 +131,25 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
           it.part_row = n_splits > 1 ? first_part + s * rc : -1;
           it.q_token0 = cu_q[i];
           const int64_t tiles = ceil_div(it.kv_end - it.kv_begin, kTileTokens);
-          keyed.push_back({it, cls, tiles * kClassCost[cls]});
+          keyed.push_back({it, group_of_rows(rc), tiles * tile_cost});
         }
       }
     }
   }
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  // grouped by kernel class (one launch each); heavy items first inside a class
+  // one launch per group; the costliest items first inside a group
   std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
-    if (a.cls != b.cls) return a.cls < b.cls;
+    if (a.group != b.group) return a.group < b.group;
     return a.cost > b.cost;
   });
   hp.items.reserve(keyed.size());
-  int32_t count[kNumClasses] = {0, 0, 0, 0, 0, 0};
+  int32_t count[kNumGroups] = {0, 0};
   for (const Keyed& k : keyed) {
     hp.items.push_back(k.it);
-    ++count[k.cls];
+    ++count[k.group];
   }
-  hp.class_begin[0] = 0;
-  for (int c = 0; c < kNumClasses; ++c) hp.class_begin[c + 1] = hp.class_begin[c] + count[c];
+  hp.group_begin[0] = 0;
+  for (int g = 0; g < kNumGroups; ++g) hp.group_begin[g + 1] = hp.group_begin[g] + count[g];
   hp.part_rows = part_rows;
   hp.workspace_bytes = (size_t)part_rows * (size_t)(p.head_dim + 2) * sizeof(float);
   return OPTIMUS_OK;

@@ -191,11 +191,12 @@ def test_plan_is_deterministic_and_longest_first_within_class():
     ia, ib = a.work_items(), b.work_items()
     assert (ia == ib).all()
     rows = ia["row_count"]
-    nt = np.where(rows <= 32, (rows + 15) // 16 - 1, 2 + (rows + 63) // 64 - 1)
-    assert (np.diff(nt) >= 0).all()  # grouped by kernel class
-    for cls in np.unique(nt):
-        tiles = (ia["kv_end"] - ia["kv_begin"] + 31)[nt == cls] // 32
-        assert (np.diff(tiles) <= 0).all()
+    group = (rows > 128).astype(int)
+    assert (np.diff(group) >= 0).all()  # grouped by launch group
+    tile_cost = np.where(rows <= 16, 1.0, np.where(rows <= 64, 1.3, (rows + 63) // 64))
+    cost = ((ia["kv_end"] - ia["kv_begin"] + 31) // 32) * tile_cost
+    for g in np.unique(group):
+        assert (np.diff(cost[group == g]) <= 1e-9).all()  # costliest first
 
 
 def test_empty_batch_and_zero_chunks():
