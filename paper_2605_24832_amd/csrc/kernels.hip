@@ -33,18 +33,43 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int W = kWavesPerBlock;
+constexpr float kMaxSlack = 8.0f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Reductions over the 4 lane groups {l, l^16, l^32, l^48} with the gfx950 lane-swap
+// instructions (plain VALU ops, no LDS-crossbar round trip).  With both operands equal to
+// v, v_permlane16_swap returns (rows 0,0,2,2 ; rows 1,1,3,3) of v (row = 16 lanes) and
+// v_permlane32_swap returns (low half twice ; high half twice); checked on the device.
+// The results are copied to scalars before the bit cast: a bit cast applied directly to a
+// vector subscript was seen to read element 0 for both.
+__device__ __forceinline__ void swap16(float v, float& x, float& y) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  x = __builtin_bit_cast(float, r0);
+  y = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ void swap32(float v, float& x, float& y) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  x = __builtin_bit_cast(float, r0);
+  y = __builtin_bit_cast(float, r1);
+}
 __device__ __forceinline__ float xor_max(float v) {
-  v = fmaxf(v, __shfl_xor(v, 16, 64));
-  v = fmaxf(v, __shfl_xor(v, 32, 64));
-  return v;
+  float x, y;
+  swap16(v, x, y);
+  v = fmaxf(x, y);
+  swap32(v, x, y);
+  return fmaxf(x, y);
 }
 __device__ __forceinline__ float xor_sum(float v) {
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+  float x, y;
+  swap16(v, x, y);
+  v = x + y;
+  swap32(v, x, y);
+  return x + y;
 }
 
 template <int D>
@@ -144,7 +169,12 @@ __device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, const bf16
     float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                      fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
     mx = xor_max(mx);
-    const float m_new = fmaxf(st.m[nt], mx * sc);
+    // The reference value m of the online softmax only has to keep exp2(s - m) in range:
+    // it follows the running maximum lazily, moving only when the maximum has grown by more
+    // than kMaxSlack (in log2 units), so p <= 2^kMaxSlack and the accumulators are rescaled
+    // on few tiles.  All lanes of a query column hold the same mx, hence take the same branch.
+    const float m_cand = fmaxf(st.m[nt], mx * sc);
+    const float m_new = (m_cand - st.m[nt] > kMaxSlack) ? m_cand : st.m[nt];  // -inf -> first finite max
     const float m_use = m_new == -INFINITY ? 0.f : m_new;  // row with no visible key so far
     const float alpha = fast_exp2(st.m[nt] - m_use);
     st.m[nt] = m_new;
@@ -158,11 +188,13 @@ __device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, const bf16
     bf16x8 pt;
 #pragma unroll
     for (int j = 0; j < 8; ++j) pt[j] = (__bf16)p[j];
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: some column moved its m
+#pragma unroll
+      for (int db = 0; db < DB; ++db) st.acc[nt][db] *= alpha;
+    }
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      f32x4 acc = st.acc[nt][db];
-      acc *= alpha;
-      st.acc[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[db], pt, acc, 0, 0, 0);
+      st.acc[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[db], pt, st.acc[nt][db], 0, 0, 0);
     }
   }
 }
