@@ -133,9 +133,15 @@ __device__ __forceinline__ void load_tile(KvTile<D>& t, int tile, const int32_t*
 template <int D, int NT>
 struct SoftmaxState {
   float m[NT];            // running max (log2 units), replicated over the 4 lane groups
-  float l[NT];            // this lane's share of the running sum
+  f32x4 lacc[NT];         // running sum of P over the keys, from an MFMA against a ones operand
+                          // (all 4 entries equal): rescaled and accumulated exactly like acc
   f32x4 acc[NT][D / 16];  // O^T: rows d = 16*db + 4*kg + j, col = query row r16
 };
+
+__device__ __forceinline__ bf16x8 ones_bf16x8() {
+  const u32x4 o = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  return __builtin_bit_cast(bf16x8, o);
+}
 
 // One 32-key tile against NT x 16 query rows, operands already in registers.
 //   k[a][s]: A operand of S^T for the a-th group of 16 keys, d step s
@@ -184,14 +190,16 @@ __device__ __forceinline__ void compute_tile(SoftmaxState<D, NT>& st, const bf16
       p[j] = fast_exp2(fmaf(s0[j], sc, -m_use));
       p[4 + j] = fast_exp2(fmaf(s1[j], sc, -m_use));
     }
-    st.l[nt] = fmaf(st.l[nt], alpha, ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])));
     bf16x8 pt;
 #pragma unroll
     for (int j = 0; j < 8; ++j) pt[j] = (__bf16)p[j];
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: some column moved its m
 #pragma unroll
       for (int db = 0; db < DB; ++db) st.acc[nt][db] *= alpha;
+      st.lacc[nt] *= alpha;
     }
+    // row sums of the bf16 P actually used in the product: one more MFMA, no VALU adds
+    st.lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones_bf16x8(), pt, st.lacc[nt], 0, 0, 0);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       st.acc[nt][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[db], pt, st.acc[nt][db], 0, 0, 0);
@@ -252,7 +260,7 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     st.m[nt] = -INFINITY;
-    st.l[nt] = 0.f;
+    st.lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int db = 0; db < DB; ++db) st.acc[nt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -322,7 +330,7 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
   // ---- merge the W waves through LDS ----
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const float lsum = xor_sum(st.l[nt]);
+    const float lsum = st.lacc[nt][0];
     if (kg == 0) {
       sm_m[wave][nt * 16 + r16] = st.m[nt];
       sm_l[wave][nt * 16 + r16] = lsum;
@@ -428,6 +436,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   constexpr int KS = D / 32, DB = D / 16, P = 1 << LGP;
   constexpr int PIECES = D * 4;        // 16-byte pieces of a K (= of a V) tile
   constexpr int LPT = PIECES / 256;    // pieces per thread per tensor per tile
+  constexpr int PF = NT <= 2 ? 2 : 1;  // register sets of prefetched tiles
   u32x4 (*sm_k)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem);
   u32x4 (*sm_v)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem + 2 * PIECES * 4);
 
@@ -465,7 +474,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     st.m[nt] = -INFINITY;
-    st.l[nt] = 0.f;
+    st.lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int db = 0; db < DB; ++db) st.acc[nt][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -502,7 +511,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
     }
   }
 
-  u32x4 rk[2][LPT], rv[2][LPT];
+  u32x4 rk[PF][LPT], rv[PF][LPT];
   auto LOAD = [&](int set, int t) {   // tile t of the item -> registers
     const int tile = tile_lo + t;
     if constexpr (LGP == 4) {
@@ -566,23 +575,42 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
     compute_tile<D, NT>(st, kop, vop, qreg, key0, key1, lim, masked, sc);
   };
 
-  // invariant at the top of iteration t: LDS buffer t%2 holds tile t; register
-  // set (t+1)%2 holds tile t+1 and set t%2 holds tile t+2 (loads in flight).
-  LOAD(0, 0);
-  if (n > 1) LOAD(1, 1);
-  STORE(0, 0);
-  if (n > 2) LOAD(0, 2);
-  __syncthreads();
-  for (int t = 0; t < n; t += 2) {
-    COMPUTE(0, t);
-    if (t + 1 < n) STORE(1, 1);
-    if (t + 3 < n) LOAD(1, t + 3);
+  // PF = 2 (narrow items, short tiles): register set p holds tiles of parity p; at the top
+  // of iteration t LDS buffer t%2 holds tile t, set (t+1)%2 tile t+1, set t%2 tile t+2.
+  // PF = 1 (wide items, long tiles, tight registers): the one set holds tile t+1.
+  if constexpr (PF == 2) {
+    LOAD(0, 0);
+    if (n > 1) LOAD(1, 1);
+    STORE(0, 0);
+    if (n > 2) LOAD(0, 2);
     __syncthreads();
-    if (t + 1 >= n) break;
-    COMPUTE(1, t + 1);
-    if (t + 2 < n) STORE(0, 0);
-    if (t + 4 < n) LOAD(0, t + 4);
+    for (int t = 0; t < n; t += 2) {
+      COMPUTE(0, t);
+      if (t + 1 < n) STORE(1, 1);
+      if (t + 3 < n) LOAD(1, t + 3);
+      __syncthreads();
+      if (t + 1 >= n) break;
+      COMPUTE(1, t + 1);
+      if (t + 2 < n) STORE(0, 0);
+      if (t + 4 < n) LOAD(0, t + 4);
+      __syncthreads();
+    }
+  } else {
+    LOAD(0, 0);
+    STORE(0, 0);
+    if (n > 1) LOAD(0, 1);
     __syncthreads();
+    for (int t = 0; t < n; t += 2) {
+      COMPUTE(0, t);
+      if (t + 1 < n) STORE(1, 0);
+      if (t + 2 < n) LOAD(0, t + 2);
+      __syncthreads();
+      if (t + 1 >= n) break;
+      COMPUTE(1, t + 1);
+      if (t + 2 < n) STORE(0, 0);
+      if (t + 3 < n) LOAD(0, t + 3);
+      __syncthreads();
+    }
   }
 
   // ---- each wave owns its rows: finish them without any cross-wave step ----
@@ -590,7 +618,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int rl = (wave * NT + nt) * 16 + r16;
-    const float lsum = xor_sum(st.l[nt]);
+    const float lsum = st.lacc[nt][0];
     if (rl >= it.row_count) continue;
     if (it.part_row >= 0) {
       float* po = a.ws_o + (int64_t)(it.part_row + rl) * D + 4 * kg;

@@ -105,8 +105,12 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
       for (int r0 = 0; r0 < rows; r0 += kMaxRowsPerItem) {
         const int rc = std::min(kMaxRowsPerItem, rows - r0);
         const double tile_cost = tile_cost_of_rows(rc);
+        // a split costs one partial (rc x (D+2) floats written, then read by the merge): keep
+        // it well below the K/V bytes the item streams (32 keys x 2 x D bf16 per tile)
+        const int64_t min_tiles_rows = std::max<int64_t>(min_tiles, (rc + 7) / 8);
         const int64_t tiles_per_item = std::min(
-            max_tiles, std::max(min_tiles, (int64_t)std::ceil(target_cost / tile_cost)));
+            std::max(max_tiles, min_tiles_rows),
+            std::max(min_tiles_rows, (int64_t)std::ceil(target_cost / tile_cost)));
         const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
         const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
         int32_t first_part = -1;
