@@ -57,9 +57,6 @@ struct optimus_attn_plan {
   // offsets (int32 units) into dev_buf
   size_t off_items = 0, off_merges = 0, off_token_req = 0, off_cu_q = 0, off_prefix = 0, off_bstart = 0;
 
-  hipStream_t side_stream = nullptr;   // default priority, runs the light group beside the heavy one
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-
   bool timing = false;
   std::vector<hipEvent_t> events;  // pairs (start, stop), created on demand
   size_t events_used = 0;
@@ -87,9 +84,6 @@ int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
     hipError_t e = hipSetDevice(device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&plan->side_stream, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&plan->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&plan->ev_join, hipEventDisableTiming);
     if (e != hipSuccess) {
       set_hip_error((int)e, "plan_create");
       optimus_attn_plan_destroy(plan);  // releases whatever was created
@@ -268,27 +262,8 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
     }
     OPT_HIP(hipEventRecord(plan->events[plan->events_used], s), "hipEventRecord");
   }
-  // The two launch groups are independent.  When both are present the light one runs on
-  // the plan's side stream, forked from and joined back into the caller's stream with
-  // events, so a ragged batch keeps the whole chip busy instead of two half-empty grids
-  // back to back.
-  const int32_t n_light = hp.group_begin[1] - hp.group_begin[0];
-  const int32_t n_heavy = hp.group_begin[2] - hp.group_begin[1];
-  if (n_light > 0 && n_heavy > 0) {
-    OPT_HIP(hipEventRecord(plan->ev_fork, s), "hipEventRecord(fork)");
-    OPT_HIP(hipStreamWaitEvent(plan->side_stream, plan->ev_fork, 0), "hipStreamWaitEvent(fork)");
-    rc = launch_attention(p, a, 1, hp.group_begin[1], n_heavy, hip_stream);
-    if (rc != OPTIMUS_OK) return rc;
-    rc = launch_attention(p, a, 0, hp.group_begin[0], n_light, plan->side_stream);
-    if (rc != OPTIMUS_OK) return rc;
-    OPT_HIP(hipEventRecord(plan->ev_join, plan->side_stream), "hipEventRecord(join)");
-    OPT_HIP(hipStreamWaitEvent(s, plan->ev_join, 0), "hipStreamWaitEvent(join)");
-  } else {
-    rc = launch_attention(p, a, 1, hp.group_begin[1], n_heavy, hip_stream);
-    if (rc != OPTIMUS_OK) return rc;
-    rc = launch_attention(p, a, 0, hp.group_begin[0], n_light, hip_stream);
-    if (rc != OPTIMUS_OK) return rc;
-  }
+  rc = launch_attention(p, a, (int32_t)hp.items.size(), hip_stream);
+  if (rc != OPTIMUS_OK) return rc;
   if (timed) {
     OPT_HIP(hipEventRecord(plan->events[plan->events_used + 1], s), "hipEventRecord");
     plan->events_used += 2;

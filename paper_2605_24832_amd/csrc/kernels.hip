@@ -653,28 +653,20 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   }
 }
 
-// One launch serves several kernel classes: the block looks at its item's row
-// count and runs the matching body, so that a ragged batch (chunk sizes 1..32
-// side by side) is one grid in longest-first order instead of one small grid
-// per class.  Two launch groups because of registers: the light group (<= 128
-// rows per item) fits 2 waves per SIMD, the heavy group (<= 256 rows) fits 1.
+// One launch serves every kind of work item: the block looks at its item's row count and
+// runs the matching body, so that a ragged batch (chunk sizes 1..32 side by side) is one
+// grid in costliest-first order instead of one small grid per kind.  All bodies fit two
+// waves per SIMD; wider items (4 subtiles per wave, one wave per SIMD) were measured slower
+// per flop than two 128-row items that share their K/V stream through the caches.
 template <int D, int LGP>
-__global__ __launch_bounds__(W * 64, 2) void attn_light_kernel(KernelArgs a, int first_item) {
+__global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
   constexpr int kFloats = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
                               ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
-  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
+  const optimus_work_item_t it = a.items[blockIdx.x];
   if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
   else if (it.row_count <= 64) lds_tile_body<D, LGP, 1>(a, it, smem);
   else lds_tile_body<D, LGP, 2>(a, it, smem);
-}
-
-template <int D, int LGP>
-__global__ __launch_bounds__(W * 64, 1) void attn_heavy_kernel(KernelArgs a, int first_item) {
-  __shared__ __attribute__((aligned(16))) float smem[lds_tile_smem_floats<D>()];
-  const optimus_work_item_t it = a.items[first_item + blockIdx.x];
-  if (it.row_count <= 192) lds_tile_body<D, LGP, 3>(a, it, smem);
-  else lds_tile_body<D, LGP, 4>(a, it, smem);
 }
 
 // Merge of split-KV partials: for each row, M = max_s m_s,
@@ -758,35 +750,27 @@ __global__ __launch_bounds__(D) void kv_append_kernel(
 
 // ------------------------------------------------------------------ launchers
 
-template <int D, int LGP>
-static int launch_attention_dp(const KernelArgs& a, int group, int32_t first_item, int32_t n_items,
-                               hipStream_t stream) {
+template <int D>
+static int launch_attention_d(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_items,
+                              hipStream_t stream) {
   const dim3 grid(n_items), block(W * 64);
-  if (group == 0) hipLaunchKernelGGL((attn_light_kernel<D, LGP>), grid, block, 0, stream, a, first_item);
-  else if (group == 1) hipLaunchKernelGGL((attn_heavy_kernel<D, LGP>), grid, block, 0, stream, a, first_item);
-  else return OPTIMUS_ERR_INVALID_ARGUMENT;
+  switch (p.page_size) {
+    case 16: hipLaunchKernelGGL((attn_kernel<D, 4>), grid, block, 0, stream, a); break;
+    case 32: hipLaunchKernelGGL((attn_kernel<D, 5>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((attn_kernel<D, 6>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((attn_kernel<D, 7>), grid, block, 0, stream, a); break;
+    default: return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
+  }
   return OPTIMUS_OK;
 }
 
-template <int D>
-static int launch_attention_d(const optimus_attn_params_t& p, const KernelArgs& a, int cls,
-                              int32_t first_item, int32_t n_items, hipStream_t stream) {
-  switch (p.page_size) {
-    case 16: return launch_attention_dp<D, 4>(a, cls, first_item, n_items, stream);
-    case 32: return launch_attention_dp<D, 5>(a, cls, first_item, n_items, stream);
-    case 64: return launch_attention_dp<D, 6>(a, cls, first_item, n_items, stream);
-    case 128: return launch_attention_dp<D, 7>(a, cls, first_item, n_items, stream);
-    default: return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
-  }
-}
-
-int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int cls,
-                     int32_t first_item, int32_t n_items, void* stream) {
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_items,
+                     void* stream) {
   if (n_items <= 0) return OPTIMUS_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int rc;
-  if (p.head_dim == 128) rc = launch_attention_d<128>(p, a, cls, first_item, n_items, s);
-  else if (p.head_dim == 64) rc = launch_attention_d<64>(p, a, cls, first_item, n_items, s);
+  if (p.head_dim == 128) rc = launch_attention_d<128>(p, a, n_items, s);
+  else if (p.head_dim == 64) rc = launch_attention_d<64>(p, a, n_items, s);
   else return OPTIMUS_ERR_UNSUPPORTED_SHAPE;
   if (rc != OPTIMUS_OK) return rc;
   hipError_t e = hipGetLastError();

@@ -13,19 +13,16 @@ namespace optimus {
 constexpr int kTileTokens = 32;     // keys per MFMA tile step (one 16x16x32 PV contraction)
 constexpr int kRowsPerSubtile = 16; // query rows per MFMA N tile
 constexpr int kWavesPerBlock = 4;
-// Launch groups.  0 "light": items of <= 128 query rows (<= 16 rows: the split-wave
-// body, the waves split the keys; 17..128 rows: the lds-tile body with 1..2 subtiles per
-// wave, the waves split the rows); 1 "heavy": 129..256 rows (lds-tile body, 3..4 subtiles).
-constexpr int kNumGroups = 2;
-constexpr int kLightMaxRows = 128;
-constexpr int kMaxRowsPerItem = 256;
-inline int group_of_rows(int rows) { return rows <= kLightMaxRows ? 0 : 1; }
-// Relative cost of one 32-key tile for an item of `rows` query rows: the narrow items are
-// bound by the K/V stream, the wide ones by MFMA + softmax work.
+// Work items by query-row count: <= 16 rows run the split-wave body (the waves split the
+// keys), 17..128 rows the lds-tile body with 1..2 subtiles per wave (the waves split the
+// rows).  A (request, kv head) pair with more rows is cut into row tiles of 128.
+constexpr int kMaxRowsPerItem = 128;
+// Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
+// scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
 inline double tile_cost_of_rows(int rows) {
   if (rows <= 16) return 1.0;
-  if (rows <= 64) return 1.3;
-  return (double)((rows + 63) / 64);
+  if (rows <= 64) return 1.1;
+  return 1.2;
 }
 
 // One merge job: `n_splits` partials of the same q tile, stored back to back
@@ -50,8 +47,7 @@ struct Tuning {
 struct HostPlan {
   int32_t batch = 0;
   int32_t total_q = 0;
-  std::vector<optimus_work_item_t> items;  // sorted by launch group, then cost (heaviest first)
-  int32_t group_begin[kNumGroups + 1] = {0, 0, 0};  // items of group g: [group_begin[g], group_begin[g+1])
+  std::vector<optimus_work_item_t> items;  // costliest first; row tiles of one key range adjacent
   std::vector<MergeItem> merges;
   std::vector<int32_t> token_req;   // [T] request of each query token
   std::vector<int32_t> cu_q, prefix_len, block_start;
@@ -87,8 +83,8 @@ struct KernelArgs {
 };
 
 // Kernel launchers (kernels.hip).  `stream` is a hipStream_t.
-int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int launch_group,
-                     int32_t first_item, int32_t n_items, void* stream);
+int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_items,
+                     void* stream);
 int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges,
                  void* stream);
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,

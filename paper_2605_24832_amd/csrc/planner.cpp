@@ -92,7 +92,11 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   const double target_cost = total_cost / (double)std::max<int64_t>(target_items, 1);
 
   // ---- emit items ----
-  struct Keyed { optimus_work_item_t it; int group; double cost; };
+  // The row tiles of one (request, kv head, key range) scan the same K/V: they are emitted
+  // next to each other (and have equal cost, so the stable sort keeps them together) and
+  // thus run at the same time on neighbouring compute units, the later ones hitting the
+  // caches instead of HBM.
+  struct Keyed { optimus_work_item_t it; double cost; };
   std::vector<Keyed> keyed;
   int64_t part_rows = 0;
   for (int i = 0; i < batch; ++i) {
@@ -101,59 +105,57 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     const int kv_len = prefix_len[i] + c;
     const int rows = c * G;
     const int n_tiles = (int)ceil_div(kv_len, kTileTokens);
+    const int n_row_tiles = (int)ceil_div(rows, kMaxRowsPerItem);
+    // all row tiles of a pair use the split of the widest one, so that their key ranges match
+    const int rc_max = std::min(kMaxRowsPerItem, rows);
+    const double tile_cost_max = tile_cost_of_rows(rc_max);
+    // a split costs one partial (rows x (D+2) floats written, then read by the merge): keep
+    // it well below the K/V bytes the item streams (32 keys x 2 x D bf16 per tile)
+    const int64_t min_tiles_rows = std::max<int64_t>(min_tiles, (rc_max + 7) / 8);
+    const int64_t tiles_per_item =
+        std::min(std::max(max_tiles, min_tiles_rows),
+                 std::max(min_tiles_rows, (int64_t)std::ceil(target_cost / tile_cost_max)));
+    const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
+    const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
     for (int g = 0; g < Hkv; ++g) {
-      for (int r0 = 0; r0 < rows; r0 += kMaxRowsPerItem) {
-        const int rc = std::min(kMaxRowsPerItem, rows - r0);
-        const double tile_cost = tile_cost_of_rows(rc);
-        // a split costs one partial (rc x (D+2) floats written, then read by the merge): keep
-        // it well below the K/V bytes the item streams (32 keys x 2 x D bf16 per tile)
-        const int64_t min_tiles_rows = std::max<int64_t>(min_tiles, (rc + 7) / 8);
-        const int64_t tiles_per_item = std::min(
-            std::max(max_tiles, min_tiles_rows),
-            std::max(min_tiles_rows, (int64_t)std::ceil(target_cost / tile_cost)));
-        const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
-        const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
-        int32_t first_part = -1;
-        if (n_splits > 1) {
-          first_part = (int32_t)part_rows;
+      std::vector<int32_t> first_part(n_row_tiles, -1);
+      if (n_splits > 1) {
+        for (int rt = 0; rt < n_row_tiles; ++rt) {
+          const int r0 = rt * kMaxRowsPerItem, rc = std::min(kMaxRowsPerItem, rows - r0);
+          first_part[rt] = (int32_t)part_rows;
           MergeItem m{};
           m.kv_head = g; m.row_begin = r0; m.row_count = rc; m.q_token0 = cu_q[i];
-          m.first_part_row = first_part; m.n_splits = n_splits;
+          m.first_part_row = first_part[rt]; m.n_splits = n_splits;
           hp.merges.push_back(m);
           part_rows += (int64_t)n_splits * rc;
         }
-        for (int s = 0; s < n_splits; ++s) {
+      }
+      for (int s = 0; s < n_splits; ++s) {
+        const int kv_begin = s * tiles_per_split * kTileTokens;
+        const int kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
+        if (kv_begin >= kv_end) {
+          // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
+          // cover all n_tiles
+          return OPTIMUS_ERR_INVALID_ARGUMENT;
+        }
+        const int64_t tiles = ceil_div(kv_end - kv_begin, kTileTokens);
+        for (int rt = 0; rt < n_row_tiles; ++rt) {
+          const int r0 = rt * kMaxRowsPerItem, rc = std::min(kMaxRowsPerItem, rows - r0);
           optimus_work_item_t it{};
           it.req = i; it.kv_head = g; it.row_begin = r0; it.row_count = rc;
-          it.kv_begin = s * tiles_per_split * kTileTokens;
-          it.kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
-          if (it.kv_begin >= it.kv_end) {
-            // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
-            // cover all n_tiles
-            return OPTIMUS_ERR_INVALID_ARGUMENT;
-          }
-          it.part_row = n_splits > 1 ? first_part + s * rc : -1;
+          it.kv_begin = kv_begin; it.kv_end = kv_end;
+          it.part_row = n_splits > 1 ? first_part[rt] + s * rc : -1;
           it.q_token0 = cu_q[i];
-          const int64_t tiles = ceil_div(it.kv_end - it.kv_begin, kTileTokens);
-          keyed.push_back({it, group_of_rows(rc), tiles * tile_cost});
+          keyed.push_back({it, tiles * tile_cost_max});
         }
       }
     }
   }
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  // one launch per group; the costliest items first inside a group
-  std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
-    if (a.group != b.group) return a.group < b.group;
-    return a.cost > b.cost;
-  });
+  std::stable_sort(keyed.begin(), keyed.end(),
+                   [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
   hp.items.reserve(keyed.size());
-  int32_t count[kNumGroups] = {0, 0};
-  for (const Keyed& k : keyed) {
-    hp.items.push_back(k.it);
-    ++count[k.group];
-  }
-  hp.group_begin[0] = 0;
-  for (int g = 0; g < kNumGroups; ++g) hp.group_begin[g + 1] = hp.group_begin[g] + count[g];
+  for (const Keyed& k : keyed) hp.items.push_back(k.it);
   hp.part_rows = part_rows;
   hp.workspace_bytes = (size_t)part_rows * (size_t)(p.head_dim + 2) * sizeof(float);
   return OPTIMUS_OK;

@@ -100,7 +100,7 @@ def coverage_check(plan, p: AttnParams, cu_q, prefix_len):
     items = plan.work_items()
     G = p.num_q_heads // p.num_kv_heads
     c = np.diff(cu_q)
-    assert (items["row_count"] >= 1).all() and (items["row_count"] <= 256).all()
+    assert (items["row_count"] >= 1).all() and (items["row_count"] <= 128).all()
     assert (items["kv_begin"] % 32 == 0).all()
     assert (items["kv_begin"] < items["kv_end"]).all()
     part_rows = []
@@ -179,7 +179,7 @@ def test_work_list_with_forced_tuning_and_odd_shapes():
 
 
 def test_plan_is_deterministic_and_longest_first_within_class():
-    p = make_params()
+    p = make_params(num_q_heads=32, num_kv_heads=4)
     rng = np.random.RandomState(5)
     L = rng.randint(1024, 8193, size=32)
     c = rng.choice([1, 2, 4, 8, 16, 32], size=32)
@@ -190,13 +190,19 @@ def test_plan_is_deterministic_and_longest_first_within_class():
     b.plan_update(cu, L, L)
     ia, ib = a.work_items(), b.work_items()
     assert (ia == ib).all()
-    rows = ia["row_count"]
-    group = (rows > 128).astype(int)
-    assert (np.diff(group) >= 0).all()  # grouped by launch group
-    tile_cost = np.where(rows <= 16, 1.0, np.where(rows <= 64, 1.3, (rows + 63) // 64))
+    # costliest first: the cost of an item is its tile count times the per-tile cost of the
+    # widest row tile of its (request, kv head) pair
+    G = p.num_q_heads // p.num_kv_heads
+    widest = np.minimum(128, c[ia["req"]] * G)
+    tile_cost = np.where(widest <= 16, 1.0, np.where(widest <= 64, 1.1, 1.2))
     cost = ((ia["kv_end"] - ia["kv_begin"] + 31) // 32) * tile_cost
-    for g in np.unique(group):
-        assert (np.diff(cost[group == g]) <= 1e-9).all()  # costliest first
+    assert (np.diff(cost) <= 1e-9).all()
+    # row tiles of one key range sit next to each other
+    wide = np.nonzero(c * G > 128)[0]
+    for i in wide[:3]:
+        idx = np.nonzero((ia["req"] == i) & (ia["kv_head"] == 0) & (ia["kv_begin"] == 0))[0]
+        assert len(idx) == -(-int(c[i]) * G // 128)
+        assert idx.max() - idx.min() == len(idx) - 1
 
 
 def test_empty_batch_and_zero_chunks():
