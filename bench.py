@@ -232,7 +232,7 @@ def main():
         roofline = {"bound": "hbm", "achieved": res["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": res["hbm_GBs"] / HBM_PEAK_GBS}
     roofline["traffic"] = load_traffic(w.name)
-    roofline["kernel"] = "attn_split_wave_kernel"
+    roofline["kernel"] = "attn_kernel"
     roofline["kernel_ms"] = res["attn_kernel_ms"]
     roofline["algorithmic_bytes_per_launch"] = res["algorithmic_bytes"]
     roofline["flops_per_launch"] = res["flops"]

@@ -14,7 +14,8 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liboptimus_attn.so")
+# OPTIMUS_ATTN_LIB points at another build of the same library (A/B measurements)
+_LIB_PATH = os.environ.get("OPTIMUS_ATTN_LIB") or os.path.join(_HERE, "liboptimus_attn.so")
 _lib = None
 
 EXPORTS = (

@@ -16,8 +16,8 @@ def sources() -> list[str]:
                   glob.glob(os.path.join(HERE, "csrc", "*.cpp")))
 
 
-def build(verbose: bool = False) -> str:
-    """Always recompiles.  Returns the path of the shared library."""
+def build(verbose: bool = False, out: str | None = None, defines: tuple = ()) -> str:
+    """Always recompiles.  Returns the path of the shared library (``out`` or the in-tree one)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -28,7 +28,8 @@ def build(verbose: bool = False) -> str:
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
     if verbose:
         cmd += ["-Rpass-analysis=kernel-resource-usage"]
-    cmd += sources() + ["-o", LIB]
+    lib = out or LIB
+    cmd += [f"-D{d}" for d in defines] + sources() + ["-o", lib]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -37,7 +38,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed building liboptimus_attn.so")
     if verbose and err.strip():
         sys.stderr.write(err + "\n")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -436,7 +436,13 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   constexpr int KS = D / 32, DB = D / 16, P = 1 << LGP;
   constexpr int PIECES = D * 4;        // 16-byte pieces of a K (= of a V) tile
   constexpr int LPT = PIECES / 256;    // pieces per thread per tensor per tile
-  constexpr int PF = NT <= 2 ? 2 : 1;  // register sets of prefetched tiles
+#ifndef OPT_PF_NT1
+#define OPT_PF_NT1 2
+#endif
+#ifndef OPT_PF_NT2
+#define OPT_PF_NT2 2
+#endif
+  constexpr int PF = NT == 1 ? OPT_PF_NT1 : OPT_PF_NT2;  // register sets of prefetched tiles
   u32x4 (*sm_k)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem);
   u32x4 (*sm_v)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem + 2 * PIECES * 4);
 
@@ -575,40 +581,23 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
     compute_tile<D, NT>(st, kop, vop, qreg, key0, key1, lim, masked, sc);
   };
 
-  // PF = 2 (narrow items, short tiles): register set p holds tiles of parity p; at the top
-  // of iteration t LDS buffer t%2 holds tile t, set (t+1)%2 tile t+1, set t%2 tile t+2.
-  // PF = 1 (wide items, long tiles, tight registers): the one set holds tile t+1.
-  if constexpr (PF == 2) {
-    LOAD(0, 0);
-    if (n > 1) LOAD(1, 1);
-    STORE(0, 0);
-    if (n > 2) LOAD(0, 2);
-    __syncthreads();
-    for (int t = 0; t < n; t += 2) {
-      COMPUTE(0, t);
-      if (t + 1 < n) STORE(1, 1);
-      if (t + 3 < n) LOAD(1, t + 3);
-      __syncthreads();
-      if (t + 1 >= n) break;
-      COMPUTE(1, t + 1);
-      if (t + 2 < n) STORE(0, 0);
-      if (t + 4 < n) LOAD(0, t + 4);
-      __syncthreads();
-    }
-  } else {
-    LOAD(0, 0);
-    STORE(0, 0);
-    if (n > 1) LOAD(0, 1);
-    __syncthreads();
-    for (int t = 0; t < n; t += 2) {
-      COMPUTE(0, t);
-      if (t + 1 < n) STORE(1, 0);
-      if (t + 2 < n) LOAD(0, t + 2);
-      __syncthreads();
-      if (t + 1 >= n) break;
-      COMPUTE(1, t + 1);
-      if (t + 2 < n) STORE(0, 0);
-      if (t + 3 < n) LOAD(0, t + 3);
+  // Software pipeline: at the top of iteration t LDS buffer t%2 holds tile t and register
+  // set (t+k)%PF holds tile t+k for k = 1..PF (global loads in flight).  The loop is
+  // unrolled by a multiple of 2 and PF so that every buffer / set index is a constant.
+  constexpr int UNROLL = (PF % 2 == 0) ? PF : 2 * PF;
+#pragma unroll
+  for (int s0 = 0; s0 < PF; ++s0)
+    if (s0 < n) LOAD(s0, s0);
+  STORE(0, 0);
+  if (PF < n) LOAD(0, PF);
+  __syncthreads();
+  for (int t = 0; t < n; t += UNROLL) {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      if (t + u >= n) break;
+      COMPUTE(u & 1, t + u);
+      if (t + u + 1 < n) STORE((u + 1) & 1, (u + 1) % PF);
+      if (t + u + 1 + PF < n) LOAD((u + 1) % PF, t + u + 1 + PF);
       __syncthreads();
     }
   }
