@@ -427,6 +427,9 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
 //      S^T products of a lane yield keys 8kg..8kg+7, the k-slots of one
 //      16-byte V^T operand;
 //   V: [key octet 0..3][d][8 keys].
+// Both are XOR-swizzled at 16-byte granularity (K: position ^ 4 in the second half of a
+// d group; V: d ^ 2*octet) so that the 8 lanes one LDS cycle serves hit 8 different
+// 16-byte bank groups on the cooperative stores as well as on the operand reads.
 template <int D>
 constexpr int lds_tile_smem_floats() { return 4 * (D * 4) * 4; }  // 2 x (K + V) tiles of D*4 x 16 bytes
 
@@ -502,9 +505,10 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   for (int i = 0; i < LPT; ++i) {
     const int e = tid + 256 * i;
     const int chunk = e >> 5, kit = e & 31;
-    kdst[i] = chunk * 32 + (((kit >> 2) & 1) << 4) + ((kit >> 3) << 2) + (kit & 3);
+    const int pos = (((kit >> 2) & 1) << 4) + ((kit >> 3) << 2) + (kit & 3);
+    kdst[i] = chunk * 32 + (pos ^ ((pos >> 4) << 2));   // bank swizzle, see the reads
     const int dd = e >> 2, q4 = e & 3;
-    vdst[i] = q4 * D + dd;
+    vdst[i] = q4 * D + (dd ^ (q4 << 1));                // bank swizzle, see the reads
     if constexpr (LGP == 4) {
       ksrc[i] = (uint32_t)(chunk * 16 + (kit & 15)) * 16u;
       vsrc[i] = (uint32_t)(dd * 32 + (q4 & 1) * 16);
@@ -558,7 +562,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       kop[0][s] = __builtin_bit_cast(bf16x8, sm_k[buf][(4 * s + kg) * 32 + r16]);
-      kop[1][s] = __builtin_bit_cast(bf16x8, sm_k[buf][(4 * s + kg) * 32 + 16 + r16]);
+      kop[1][s] = __builtin_bit_cast(bf16x8, sm_k[buf][(4 * s + kg) * 32 + 16 + (r16 ^ 4)]);
     }
     if (masked) {
       const int cnt = it.kv_end - key0;
@@ -566,14 +570,14 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
                      m3 = keep_mask(cnt - 6);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        u32x4 vv = sm_v[buf][kg * D + 16 * db + r16];
+        u32x4 vv = sm_v[buf][kg * D + 16 * db + (r16 ^ (kg << 1))];
         vv.x &= m0; vv.y &= m1; vv.z &= m2; vv.w &= m3;
         vop[db] = __builtin_bit_cast(bf16x8, vv);
       }
     } else {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
-        vop[db] = __builtin_bit_cast(bf16x8, sm_v[buf][kg * D + 16 * db + r16]);
+        vop[db] = __builtin_bit_cast(bf16x8, sm_v[buf][kg * D + 16 * db + (r16 ^ (kg << 1))]);
     }
     int lim[NT];
 #pragma unroll
