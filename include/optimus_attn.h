@@ -88,7 +88,7 @@ typedef struct {
   int32_t req;         /* request index i                                       */
   int32_t kv_head;     /* g                                                     */
   int32_t row_begin;   /* first row of this q tile                              */
-  int32_t row_count;   /* rows in this q tile (1..64)                           */
+  int32_t row_count;   /* rows in this q tile (1..128)                          */
   int32_t kv_begin;    /* first logical key slot, multiple of 32                */
   int32_t kv_end;      /* one past the last key slot, <= L_i + c_i              */
   int32_t part_row;    /* -1: writes final output; else first row of its partial

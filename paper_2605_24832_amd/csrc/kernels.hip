@@ -2,20 +2,29 @@
 // (Optimus Sec. 6: paged attention over variable-length query chunks, plus
 // the mapping of per-chunk KV into the paged cache).
 //
-// attention main kernel ("split-wave"):
-//   One workgroup of 4 wave64 per work item = (request, kv head, <=64 query
-//   rows, key range).  The rows of a (request, kv head) pair are all G query
-//   heads of the group x the chunk tokens, so K/V are fetched once per group.
-//   The 4 waves take the 32-key tiles of the range round-robin; each wave keeps
-//   its own online-softmax state and the waves are merged through LDS at the
-//   end.  K and V go from HBM straight into MFMA operand registers: the pool
-//   layout (K in 16-byte d-groups, slot-major; V slot-contiguous) makes every
-//   wave-wide load a contiguous run, and the transposed formulation
+// One attention kernel, one workgroup of 4 wave64 per work item = (request, kv
+// head, <= 128 query rows, key range).  The rows of a (request, kv head) pair
+// are all G query heads of the group x the chunk tokens, so K/V are fetched
+// once per group.  Both products are transposed,
 //       S^T = K Q^T   (v_mfma_f32_16x16x32_bf16, A = K tile, B = Q^T)
 //       O^T = V^T P^T (A = V^T tile, B = P^T)
-//   leaves the S^T accumulator of a lane exactly in the B-operand layout the
-//   second product needs, so P never moves between lanes; only the row max
-//   crosses lanes (two xor shuffles over the 4 lane groups).
+// which leaves the S^T accumulator of a lane exactly in the B-operand layout
+// the second product needs, so P never moves between lanes; only the row max
+// crosses lanes (two lane-swap steps over the 4 lane groups), and the row sum
+// comes out of one more MFMA against a ones operand.
+//
+//   <= 16 rows ("split-wave" body): the 4 waves take the 32-key tiles of the
+//   range round-robin, K and V go from HBM straight into MFMA operand
+//   registers (the pool layout, K in 16-byte d-groups slot-major and V
+//   slot-contiguous, makes every wave-wide load a contiguous run), each wave
+//   keeps its own online-softmax state and the waves are merged through LDS.
+//
+//   17..128 rows ("lds-tile" body): all waves walk the same tiles, staged once
+//   per workgroup in LDS, and each wave owns 16 or 32 of the rows.
+//
+// Key ranges split over several work items leave partials that the merge
+// kernel combines (a fused "last block merges" variant was measured 4x slower:
+// a device-scope fence on this multi-die part writes back and invalidates L2).
 //
 // 16x16x32 bf16 MFMA register layout (lane = 16*kg + r, kg 0..3, r 0..15):
 //   A: row r,  k = 8*kg .. 8*kg+7      B: col r, k = 8*kg .. 8*kg+7

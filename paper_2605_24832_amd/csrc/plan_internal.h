@@ -17,6 +17,7 @@ constexpr int kWavesPerBlock = 4;
 // keys), 17..128 rows the lds-tile body with 1..2 subtiles per wave (the waves split the
 // rows).  A (request, kv head) pair with more rows is cut into row tiles of 128.
 constexpr int kMaxRowsPerItem = 128;
+constexpr int kNumXcd = 8;  // accelerator dies of an MI355X; workgroup i runs on die i % 8
 // Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
 // scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
 inline double tile_cost_of_rows(int rows) {
@@ -47,7 +48,7 @@ struct Tuning {
 struct HostPlan {
   int32_t batch = 0;
   int32_t total_q = 0;
-  std::vector<optimus_work_item_t> items;  // costliest first; row tiles of one key range adjacent
+  std::vector<optimus_work_item_t> items;  // costliest first, interleaved over 8 XCD lanes
   std::vector<MergeItem> merges;
   std::vector<int32_t> token_req;   // [T] request of each query token
   std::vector<int32_t> cu_q, prefix_len, block_start;

@@ -154,8 +154,31 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
   std::stable_sort(keyed.begin(), keyed.end(),
                    [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
+  // Workgroups go to the 8 XCDs (each with its own L2) round-robin by index.  Sibling row
+  // tiles (same request, kv head and key range; adjacent after the stable sort) are put
+  // into one of 8 lanes and the lanes are emitted interleaved, so siblings land on the same
+  // XCD at indices p, p+8, ...: the second one finds the K/V stream in that XCD's L2.  The
+  // lane is the one with the least cost so far, which also balances the XCDs.
+  std::vector<Keyed> lanes[kNumXcd];
+  double lane_cost[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (size_t k = 0; k < keyed.size();) {
+    size_t e = k + 1;
+    while (e < keyed.size() && keyed[e].it.req == keyed[k].it.req &&
+           keyed[e].it.kv_head == keyed[k].it.kv_head && keyed[e].it.kv_begin == keyed[k].it.kv_begin)
+      ++e;
+    int best = 0;
+    for (int x = 1; x < kNumXcd; ++x)
+      if (lane_cost[x] < lane_cost[best]) best = x;
+    for (size_t j = k; j < e; ++j) {
+      lanes[best].push_back(keyed[j]);
+      lane_cost[best] += keyed[j].cost;
+    }
+    k = e;
+  }
   hp.items.reserve(keyed.size());
-  for (const Keyed& k : keyed) hp.items.push_back(k.it);
+  for (size_t depth = 0; hp.items.size() < keyed.size(); ++depth)
+    for (int x = 0; x < kNumXcd; ++x)
+      if (depth < lanes[x].size()) hp.items.push_back(lanes[x][depth].it);
   hp.part_rows = part_rows;
   hp.workspace_bytes = (size_t)part_rows * (size_t)(p.head_dim + 2) * sizeof(float);
   return OPTIMUS_OK;
