@@ -45,6 +45,7 @@ struct Tuning {
 };
 
 // Result of host planning for one iteration.
+struct PlanGroup;  // planner-private
 struct HostPlan {
   int32_t batch = 0;
   int32_t total_q = 0;
@@ -54,6 +55,18 @@ struct HostPlan {
   std::vector<int32_t> cu_q, prefix_len, block_start;
   int64_t part_rows = 0;            // rows of split-KV partials in the workspace
   size_t workspace_bytes = 0;
+  // planner scratch, kept for its capacity
+  std::vector<int32_t> req_first_merge, scratch_order;
+  std::vector<int8_t> scratch_lane;
+  std::vector<uint64_t> scratch_keys;
+  struct Group { int32_t req, kv_head, kv_begin, kv_end, split, n_splits, n_row_tiles; double cost; };
+  std::vector<Group> scratch_groups;
+
+  void reset() {
+    batch = 0; total_q = 0; part_rows = 0; workspace_bytes = 0;
+    items.clear(); merges.clear(); token_req.clear(); cu_q.clear(); prefix_len.clear();
+    block_start.clear();
+  }
 };
 
 // Pure host code: validate the descriptors and build the work list.

@@ -39,7 +39,7 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   if (batch < 0 || !out) return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (batch > 0 && (!cu_q || !prefix_len || !block_start)) return OPTIMUS_ERR_INVALID_ARGUMENT;
   HostPlan& hp = *out;
-  hp = HostPlan();
+  hp.reset();  // keeps the vectors' capacity: planning runs every iteration
   hp.batch = batch;
   if (batch == 0) return OPTIMUS_OK;
 
@@ -60,8 +60,9 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     if (c > 0 && need > p.max_pages_per_req) return OPTIMUS_ERR_BLOCK_TABLE_TOO_SHORT;
     if (block_table && c > 0) {
       const int32_t* row = block_table + (int64_t)i * p.max_pages_per_req;
-      for (int64_t k = 0; k < need; ++k)
-        if (row[k] < 0 || row[k] >= p.num_pages) return OPTIMUS_ERR_PAGE_OUT_OF_RANGE;
+      uint32_t worst = 0;  // as unsigned, a negative id is larger than any valid one
+      for (int64_t k = 0; k < need; ++k) worst = std::max(worst, (uint32_t)row[k]);
+      if (worst >= (uint32_t)p.num_pages) return OPTIMUS_ERR_PAGE_OUT_OF_RANGE;
     }
   }
 
@@ -91,14 +92,19 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
       min_tiles, (tuning.max_split_tokens > 0 ? tuning.max_split_tokens : 8192) / kTileTokens);
   const double target_cost = total_cost / (double)std::max<int64_t>(target_items, 1);
 
-  // ---- emit items ----
-  // The row tiles of one (request, kv head, key range) scan the same K/V: they are emitted
-  // next to each other (and have equal cost, so the stable sort keeps them together) and
-  // thus run at the same time on neighbouring compute units, the later ones hitting the
-  // caches instead of HBM.
-  struct Keyed { optimus_work_item_t it; double cost; };
-  std::vector<Keyed> keyed;
+  // ---- sibling groups ----
+  // A group = the row tiles of one (request, kv head, key range): same K/V stream, same
+  // cost.  Groups are sorted costliest first and dealt to 8 lanes (always the lane with
+  // the least cost so far); lane x is emitted at work-list indices x, x+8, x+16, ...
+  // Workgroups go to the 8 XCDs (each with its own L2) round-robin by index, so the row
+  // tiles of a group run at the same time on the same XCD and the later ones find the K/V
+  // stream in that XCD's L2; the dealing also balances the XCDs.
+  using Group = HostPlan::Group;
+  std::vector<Group>& groups = hp.scratch_groups;
+  groups.clear();
   int64_t part_rows = 0;
+  size_t n_items = 0;
+  hp.req_first_merge.assign(batch, -1);
   for (int i = 0; i < batch; ++i) {
     const int c = cu_q[i + 1] - cu_q[i];
     if (c == 0) continue;
@@ -108,77 +114,95 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     const int n_row_tiles = (int)ceil_div(rows, kMaxRowsPerItem);
     // all row tiles of a pair use the split of the widest one, so that their key ranges match
     const int rc_max = std::min(kMaxRowsPerItem, rows);
-    const double tile_cost_max = tile_cost_of_rows(rc_max);
+    const double tile_cost = tile_cost_of_rows(rc_max);
     // a split costs one partial (rows x (D+2) floats written, then read by the merge): keep
     // it well below the K/V bytes the item streams (32 keys x 2 x D bf16 per tile)
     const int64_t min_tiles_rows = std::max<int64_t>(min_tiles, (rc_max + 7) / 8);
     const int64_t tiles_per_item =
         std::min(std::max(max_tiles, min_tiles_rows),
-                 std::max(min_tiles_rows, (int64_t)std::ceil(target_cost / tile_cost_max)));
+                 std::max(min_tiles_rows, (int64_t)std::ceil(target_cost / tile_cost)));
     const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
     const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
-    for (int g = 0; g < Hkv; ++g) {
-      std::vector<int32_t> first_part(n_row_tiles, -1);
-      if (n_splits > 1) {
+    if (n_splits > 1) {
+      // merge jobs and partial rows of this request: [kv head][row tile], splits back to back
+      hp.req_first_merge[i] = (int32_t)hp.merges.size();
+      for (int g = 0; g < Hkv; ++g)
         for (int rt = 0; rt < n_row_tiles; ++rt) {
           const int r0 = rt * kMaxRowsPerItem, rc = std::min(kMaxRowsPerItem, rows - r0);
-          first_part[rt] = (int32_t)part_rows;
           MergeItem m{};
           m.kv_head = g; m.row_begin = r0; m.row_count = rc; m.q_token0 = cu_q[i];
-          m.first_part_row = first_part[rt]; m.n_splits = n_splits;
+          m.first_part_row = (int32_t)part_rows; m.n_splits = n_splits;
           hp.merges.push_back(m);
           part_rows += (int64_t)n_splits * rc;
         }
-      }
-      for (int s = 0; s < n_splits; ++s) {
-        const int kv_begin = s * tiles_per_split * kTileTokens;
-        const int kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
-        if (kv_begin >= kv_end) {
-          // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
-          // cover all n_tiles
-          return OPTIMUS_ERR_INVALID_ARGUMENT;
-        }
-        const int64_t tiles = ceil_div(kv_end - kv_begin, kTileTokens);
-        for (int rt = 0; rt < n_row_tiles; ++rt) {
-          const int r0 = rt * kMaxRowsPerItem, rc = std::min(kMaxRowsPerItem, rows - r0);
-          optimus_work_item_t it{};
-          it.req = i; it.kv_head = g; it.row_begin = r0; it.row_count = rc;
-          it.kv_begin = kv_begin; it.kv_end = kv_end;
-          it.part_row = n_splits > 1 ? first_part[rt] + s * rc : -1;
-          it.q_token0 = cu_q[i];
-          keyed.push_back({it, tiles * tile_cost_max});
-        }
-      }
     }
+    for (int s = 0; s < n_splits; ++s) {
+      const int kv_begin = s * tiles_per_split * kTileTokens;
+      const int kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
+      if (kv_begin >= kv_end) {
+        // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
+        // cover all n_tiles
+        return OPTIMUS_ERR_INVALID_ARGUMENT;
+      }
+      const double cost = (double)ceil_div(kv_end - kv_begin, kTileTokens) * tile_cost;
+      for (int g = 0; g < Hkv; ++g)
+        groups.push_back({i, g, kv_begin, kv_end, s, n_splits, n_row_tiles, cost});
+    }
+    n_items += (size_t)n_splits * Hkv * n_row_tiles;
   }
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  std::stable_sort(keyed.begin(), keyed.end(),
-                   [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
-  // Workgroups go to the 8 XCDs (each with its own L2) round-robin by index.  Sibling row
-  // tiles (same request, kv head and key range; adjacent after the stable sort) are put
-  // into one of 8 lanes and the lanes are emitted interleaved, so siblings land on the same
-  // XCD at indices p, p+8, ...: the second one finds the K/V stream in that XCD's L2.  The
-  // lane is the one with the least cost so far, which also balances the XCDs.
-  std::vector<Keyed> lanes[kNumXcd];
+  // costliest first; ties keep the emission order (request, split, kv head) for determinism
+  // (sorted as packed integers: inverted cost in tenths of a tile in the high half, emission
+  // index in the low half)
+  std::vector<uint64_t>& keys = hp.scratch_keys;
+  keys.resize(groups.size());
+  for (size_t k = 0; k < keys.size(); ++k)
+    keys[k] = ((uint64_t)(0xffffffffu - (uint32_t)std::lround(groups[k].cost * 10.0)) << 32) | (uint64_t)k;
+  std::sort(keys.begin(), keys.end());
+  std::vector<int32_t>& order = hp.scratch_order;
+  order.resize(groups.size());
+  for (size_t k = 0; k < order.size(); ++k) order[k] = (int32_t)(keys[k] & 0xffffffffu);
+  // deal the groups to the lanes: first pass sizes the lanes, second pass places the items
   double lane_cost[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (size_t k = 0; k < keyed.size();) {
-    size_t e = k + 1;
-    while (e < keyed.size() && keyed[e].it.req == keyed[k].it.req &&
-           keyed[e].it.kv_head == keyed[k].it.kv_head && keyed[e].it.kv_begin == keyed[k].it.kv_begin)
-      ++e;
+  size_t lane_len[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
+  std::vector<int8_t>& lane_of = hp.scratch_lane;
+  lane_of.resize(groups.size());
+  for (int32_t gi : order) {
     int best = 0;
     for (int x = 1; x < kNumXcd; ++x)
       if (lane_cost[x] < lane_cost[best]) best = x;
-    for (size_t j = k; j < e; ++j) {
-      lanes[best].push_back(keyed[j]);
-      lane_cost[best] += keyed[j].cost;
-    }
-    k = e;
+    lane_of[gi] = (int8_t)best;
+    lane_cost[best] += groups[gi].cost * groups[gi].n_row_tiles;
+    lane_len[best] += groups[gi].n_row_tiles;
   }
-  hp.items.reserve(keyed.size());
-  for (size_t depth = 0; hp.items.size() < keyed.size(); ++depth)
-    for (int x = 0; x < kNumXcd; ++x)
-      if (depth < lanes[x].size()) hp.items.push_back(lanes[x][depth].it);
+  // work-list index of depth d in lane x = number of items at smaller (depth, lane): lanes
+  // shorter than d have dropped out of the round-robin
+  auto index_of = [&](int x, size_t d) {
+    size_t idx = 0;
+    for (int y = 0; y < kNumXcd; ++y) idx += std::min(lane_len[y], d);  // full rounds before depth d
+    for (int y = 0; y < x; ++y) idx += lane_len[y] > d ? 1 : 0;        // lanes before x in round d
+    return idx;
+  };
+  hp.items.resize(n_items);
+  size_t lane_fill[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int32_t gi : order) {
+    const Group& gr = groups[gi];
+    const int x = lane_of[gi];
+    const int rows = (cu_q[gr.req + 1] - cu_q[gr.req]) * G;
+    for (int rt = 0; rt < gr.n_row_tiles; ++rt) {
+      const int r0 = rt * kMaxRowsPerItem, rc = std::min(kMaxRowsPerItem, rows - r0);
+      optimus_work_item_t it{};
+      it.req = gr.req; it.kv_head = gr.kv_head; it.row_begin = r0; it.row_count = rc;
+      it.kv_begin = gr.kv_begin; it.kv_end = gr.kv_end;
+      it.q_token0 = cu_q[gr.req];
+      it.part_row = -1;
+      if (gr.n_splits > 1) {
+        const MergeItem& m = hp.merges[hp.req_first_merge[gr.req] + gr.kv_head * gr.n_row_tiles + rt];
+        it.part_row = m.first_part_row + gr.split * rc;
+      }
+      hp.items[index_of(x, lane_fill[x]++)] = it;
+    }
+  }
   hp.part_rows = part_rows;
   hp.workspace_bytes = (size_t)part_rows * (size_t)(p.head_dim + 2) * sizeof(float);
   return OPTIMUS_OK;
