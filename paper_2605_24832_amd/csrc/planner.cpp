@@ -136,22 +136,25 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
           part_rows += (int64_t)n_splits * rc;
         }
     }
-    for (int s = 0; s < n_splits; ++s) {
-      const int kv_begin = s * tiles_per_split * kTileTokens;
-      const int kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
-      if (kv_begin >= kv_end) {
-        // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
-        // cover all n_tiles
-        return OPTIMUS_ERR_INVALID_ARGUMENT;
-      }
-      const double cost = (double)ceil_div(kv_end - kv_begin, kTileTokens) * tile_cost;
-      for (int g = 0; g < Hkv; ++g)
+    // emission order (request, kv head, split): with equal costs the dealing below then
+    // spreads the kv heads of a request over the XCDs instead of pinning head x to XCD x
+    // (measured a few percent faster: the heads sit at fixed offsets inside every page)
+    for (int g = 0; g < Hkv; ++g)
+      for (int s = 0; s < n_splits; ++s) {
+        const int kv_begin = s * tiles_per_split * kTileTokens;
+        const int kv_end = std::min(kv_len, (s + 1) * tiles_per_split * kTileTokens);
+        if (kv_begin >= kv_end) {
+          // cannot happen: tiles_per_split <= tiles_per_item, so (n_splits-1) splits never
+          // cover all n_tiles
+          return OPTIMUS_ERR_INVALID_ARGUMENT;
+        }
+        const double cost = (double)ceil_div(kv_end - kv_begin, kTileTokens) * tile_cost;
         groups.push_back({i, g, kv_begin, kv_end, s, n_splits, n_row_tiles, cost});
-    }
+      }
     n_items += (size_t)n_splits * Hkv * n_row_tiles;
   }
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  // costliest first; ties keep the emission order (request, split, kv head) for determinism
+  // costliest first; ties keep the emission order for determinism
   // (sorted as packed integers: inverted cost in tenths of a tile in the high half, emission
   // index in the low half)
   std::vector<uint64_t>& keys = hp.scratch_keys;

@@ -228,6 +228,31 @@ def test_constant_v_and_single_token_decode(oracle_mod):
     assert err <= 2.0 * 2 ** -8, err  # one bf16 rounding of |v| <= 2
 
 
+def test_append_overwrites_provisional_slots(oracle_mod):
+    """Chunk KV is provisional: after commit the final KV of the same tokens is written over
+    the same slots (Sec. 4.1).  A second append to the same slots must win, bit for bit,
+    and attention must then see the new rows."""
+    _say("overwrite")
+    kw = dict(seed=43, num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16, block_size=32,
+              prefix_len=[70, 9], chunk=[5, 12], block_inner=[0, 0], device=DEV)
+    w = inputs.make_workload("ow", **kw)
+    bits0 = hp.host_bits(w)
+    hp.run_hip(w)                                  # first append: provisional rows
+    # second pass over the same slots with different K/V (the "committed" rows)
+    g = torch.Generator(device=DEV); g.manual_seed(99)
+    w.k_new = torch.randn(w.k_new.shape, generator=g, device=DEV).to(torch.bfloat16)
+    w.v_new = torch.randn(w.v_new.shape, generator=g, device=DEV).to(torch.bfloat16)
+    out, _ = hp.run_hip(w)
+    bits1 = hp.host_bits(w)
+    kp, vp = bits0["k_pool"].copy(), bits0["v_pool"].copy()
+    p = hp.oracle_params(oracle_mod, w)
+    oracle_mod.kv_append(p, w.cu_q, w.prefix_len, w.block_table, bits1["k_new"], bits1["v_new"], kp, vp)
+    np.testing.assert_array_equal(bits1["k_pool"], kp)
+    np.testing.assert_array_equal(bits1["v_pool"], vp)
+    ref, _, _ = hp.run_oracle(oracle_mod, w, bits=dict(bits0, k_new=bits1["k_new"], v_new=bits1["v_new"]))
+    hp.check_close(out.float().cpu().numpy(), ref, what="overwrite")
+
+
 def test_empty_batches():
     _say("empty")
     w = inputs.make_workload("empty", seed=37, num_q_heads=8, num_kv_heads=2, head_dim=128,
