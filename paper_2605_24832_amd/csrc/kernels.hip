@@ -87,25 +87,40 @@ struct KvTile {
   u32x2 v[D / 16][2];    // [16-wide d block][16-key half] : 4 keys x bf16
 };
 
-// Issue the loads of one 32-key tile.  `bt` is the request's block-table row,
-// `last_page` the index of the last page that holds a key of this request.
+// Page ids of one 32-key tile (two pages at P = 16, else one).
+struct TilePages { int32_t p0, p1; };
+
+// `bt` is the request's block-table row, `last_page` the index of the last page that holds
+// a key of this item, `tile_max` the item's last tile.  The tile index is clamped so that a
+// look-ahead past the end still reads a valid entry.
+template <int LGP>
+__device__ __forceinline__ TilePages tile_pages(const int32_t* __restrict__ bt, int tile, int tile_max,
+                                                int last_page) {
+  tile = min(tile, tile_max);
+  if constexpr (LGP == 4) {
+    // the second page may lie beyond the request's last page (then its keys are all
+    // masked): clamp so the loads stay in a valid page
+    const int pi0 = tile * 2;
+    return TilePages{bt[pi0], bt[min(pi0 + 1, last_page)]};
+  } else {
+    const int32_t pg = bt[(tile * kTileTokens) >> LGP];
+    return TilePages{pg, pg};
+  }
+}
+
+// Issue the loads of one 32-key tile whose page ids are already known.
 template <int D, int LGP>
-__device__ __forceinline__ void load_tile(KvTile<D>& t, int tile, const int32_t* __restrict__ bt,
-                                          int last_page, const char* __restrict__ kbase,
+__device__ __forceinline__ void load_tile(KvTile<D>& t, int tile, TilePages pg,
+                                          const char* __restrict__ kbase,
                                           const char* __restrict__ vbase, int64_t k_stride_page_b,
                                           int64_t v_stride_page_b, int r16, int kg) {
   constexpr int P = 1 << LGP;
   constexpr int KS = D / 32, DB = D / 16;
   if constexpr (LGP == 4) {
-    // two pages per tile; the second may lie beyond the request's last page
-    // (then its keys are all masked): clamp so the load stays in a valid page.
-    const int pi0 = tile * 2;
-    const int pi1 = min(pi0 + 1, last_page);
-    const int64_t pg0 = bt[pi0], pg1 = bt[pi1];
-    const char* k0 = kbase + pg0 * k_stride_page_b;
-    const char* k1 = kbase + pg1 * k_stride_page_b;
-    const char* v0 = vbase + pg0 * v_stride_page_b;
-    const char* v1 = vbase + pg1 * v_stride_page_b;
+    const char* k0 = kbase + (int64_t)pg.p0 * k_stride_page_b;
+    const char* k1 = kbase + (int64_t)pg.p1 * k_stride_page_b;
+    const char* v0 = vbase + (int64_t)pg.p0 * v_stride_page_b;
+    const char* v1 = vbase + (int64_t)pg.p1 * v_stride_page_b;
     const uint32_t koff = (uint32_t)(kg * P + r16) * 16u;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -119,11 +134,9 @@ __device__ __forceinline__ void load_tile(KvTile<D>& t, int tile, const int32_t*
       t.v[db][1] = *reinterpret_cast<const u32x2*>(v1 + voff + db * (16 * P * 2));
     }
   } else {
-    const int pi = (tile * kTileTokens) >> LGP;
     const int slot0 = (tile * kTileTokens) & (P - 1);
-    const int64_t pg = bt[pi];
-    const char* k0 = kbase + pg * k_stride_page_b;
-    const char* v0 = vbase + pg * v_stride_page_b;
+    const char* k0 = kbase + (int64_t)pg.p0 * k_stride_page_b;
+    const char* v0 = vbase + (int64_t)pg.p0 * v_stride_page_b;
     const uint32_t koff = (uint32_t)(kg * P + slot0 + r16) * 16u;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -288,8 +301,9 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
   const int t0 = tile_lo + wave;
 
   KvTile<D> ta, tb;
-  auto LOAD = [&](KvTile<D>& t, int i) {
-    load_tile<D, LGP>(t, t0 + W * i, bt, last_page, kbase, vbase, kspb, vspb, r16, kg);
+  auto PAGES = [&](int i) { return tile_pages<LGP>(bt, t0 + W * i, tile_hi - 1, last_page); };
+  auto LOAD = [&](KvTile<D>& t, int i, TilePages pg) {
+    load_tile<D, LGP>(t, t0 + W * i, pg, kbase, vbase, kspb, vspb, r16, kg);
   };
   auto COMPUTE = [&](KvTile<D>& t, int i) {
     const int key_base = (t0 + W * i) * kTileTokens;
@@ -317,18 +331,26 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
     for (int nt = 0; nt < NT; ++nt) lim[nt] = min(it.kv_end, vis_end[nt]);
     compute_tile<D, NT>(st, t.k, vop, qreg, key0, key1, lim, masked, sc);
   };
+  // Page ids are fetched two tiles ahead of their K/V loads: the memory counter retires in
+  // order, so an id requested right before its use would wait behind the whole previous
+  // tile and the next tile's loads could not be issued until that one had arrived.
   if (n > 0) {
-    LOAD(ta, 0);
+    TilePages p0 = PAGES(0), p1 = PAGES(1), p2 = PAGES(2);
+    LOAD(ta, 0, p0);
     int i = 0;
     while (i + 2 < n) {
-      LOAD(tb, i + 1);
+      const TilePages p3 = PAGES(i + 3);
+      LOAD(tb, i + 1, p1);
       COMPUTE(ta, i);
-      LOAD(ta, i + 2);
+      const TilePages p4 = PAGES(i + 4);
+      LOAD(ta, i + 2, p2);
       COMPUTE(tb, i + 1);
+      p1 = p3;
+      p2 = p4;
       i += 2;
     }
     if (i + 1 < n) {
-      LOAD(tb, i + 1);
+      LOAD(tb, i + 1, p1);
       COMPUTE(ta, i);
       COMPUTE(tb, i + 1);
     } else {
@@ -533,21 +555,19 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   u32x4 rk[PF][LPT], rv[PF][LPT];
   auto LOAD = [&](int set, int t) {   // tile t of the item -> registers
     const int tile = tile_lo + t;
+    const TilePages pg = tile_pages<LGP>(bt, tile, tile_lo + n - 1, last_page);
     if constexpr (LGP == 4) {
-      const int pi0 = tile * 2, pi1 = min(pi0 + 1, last_page);
-      const int64_t pg0 = bt[pi0], pg1 = bt[pi1];
 #pragma unroll
       for (int i = 0; i < LPT; ++i) {
-        const char* kp = kbase + (second_page[i][0] ? pg1 : pg0) * kspb;
-        const char* vp = vbase + (second_page[i][1] ? pg1 : pg0) * vspb;
+        const char* kp = kbase + (int64_t)(second_page[i][0] ? pg.p1 : pg.p0) * kspb;
+        const char* vp = vbase + (int64_t)(second_page[i][1] ? pg.p1 : pg.p0) * vspb;
         rk[set][i] = *reinterpret_cast<const u32x4*>(kp + ksrc[i]);
         rv[set][i] = *reinterpret_cast<const u32x4*>(vp + vsrc[i]);
       }
     } else {
-      const int64_t pg = bt[(tile * kTileTokens) >> LGP];
       const uint32_t slot0 = (uint32_t)((tile * kTileTokens) & (P - 1));
-      const char* kp = kbase + pg * kspb + slot0 * 16u;
-      const char* vp = vbase + pg * vspb + slot0 * 2u;
+      const char* kp = kbase + (int64_t)pg.p0 * kspb + slot0 * 16u;
+      const char* vp = vbase + (int64_t)pg.p0 * vspb + slot0 * 2u;
 #pragma unroll
       for (int i = 0; i < LPT; ++i) {
         rk[set][i] = *reinterpret_cast<const u32x4*>(kp + ksrc[i]);
@@ -563,6 +583,9 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
     }
   };
   auto COMPUTE = [&](int buf, int t) {
+#ifdef OPT_EXPERIMENT_SKIP_COMPUTE
+    if (a.scale_log2 != -1.f) return;   // timing experiment only: results are wrong
+#endif
     if (!wave_has_rows) return;
     const int key_base = (tile_lo + t) * kTileTokens;
     const bool masked = key_base + kTileTokens > mask_from;
@@ -604,7 +627,21 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   STORE(0, 0);
   if (PF < n) LOAD(0, PF);
   __syncthreads();
-  for (int t = 0; t < n; t += UNROLL) {
+  // Steady state without a branch between the issue of a tile's loads and their use, so the
+  // memory-counter waits the compiler inserts are exact (a conditional load makes it wait for
+  // every outstanding load, which would undo the prefetch); the last tiles run in the
+  // guarded loop below.
+  int t = 0;
+  for (; t + UNROLL + PF < n; t += UNROLL) {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      COMPUTE(u & 1, t + u);
+      STORE((u + 1) & 1, (u + 1) % PF);
+      LOAD((u + 1) % PF, t + u + 1 + PF);
+      __syncthreads();
+    }
+  }
+  for (; t < n; t += UNROLL) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       if (t + u >= n) break;
