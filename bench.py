@@ -190,6 +190,55 @@ def cpu_baseline(w, runner, budget_s: float = 15.0):
         "checked_tokens": int(len(tok))}
 
 
+def measure_commit(device: str, steps: int = 20):
+    """The commit step on the chunk tokens of the default workload: 604 rows
+    of a 151936-entry bf16 vocabulary.  HBM-bound scan: algorithmic bytes = T * V * 2."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2605_24832_amd import commit_forward, commit_params, commit_workspace_bytes, inputs
+    rng = np.random.RandomState(inputs.BASE_SEED + 3)
+    rng.randint(1024, 8193, size=256)
+    c = rng.choice([1, 2, 4], size=256)
+    cu_h = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    T, V = int(cu_h[-1]), 151936
+    # rotate over copies so the 184 MB of logits are not served by the 256 MB memory-side cache
+    xs = [inputs.make_logits(T, V, seed=inputs.BASE_SEED + 40 + k, device=device) for k in range(4)]
+    p = commit_params(T, V, xs[0].shape[1], 0.9, 256, 1)
+    ws = torch.empty(commit_workspace_bytes(p) // 4 + 4, dtype=torch.float32, device=device)
+    cu = torch.as_tensor(cu_h, device=device)
+    tok = torch.empty(T, dtype=torch.int32, device=device)
+    conf = torch.empty(T, dtype=torch.float32, device=device)
+    com = torch.empty(T, dtype=torch.int32, device=device)
+    for k in range(4):
+        commit_forward(p, xs[k], cu, tok, conf, com, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(steps):
+        commit_forward(p, xs[k % 4], cu, tok, conf, com, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    last = xs[(steps - 1) % 4]
+    t0 = time.perf_counter()
+    rt, rc, rcom = oracle.commit(inputs.to_bits(last), V, 0.9, cu_h, 1)
+    cpu_s = time.perf_counter() - t0
+    alg = T * V * 2
+    return {
+        "workload": f"commit step: {T} chunk tokens x vocab {V}, bf16 logits, threshold 0.9, 256 requests",
+        "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3), "algorithmic_bytes": alg,
+        "hbm_GBs": alg / (ms * 1e-3) / 1e9, "roofline_frac_hbm": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "committed": int(com.sum().item()),
+        "cpu_oracle": {"value": T / cpu_s, "unit": "tokens/s", "cores": int(oracle.num_threads())},
+        "parity_vs_oracle": {
+            "tokens_equal": bool((tok.cpu().numpy() == rt).all()),
+            "max_rel_conf_err": float(np.max(np.abs(conf.cpu().numpy() - rc) / rc)),
+            "commit_flags_differing": int((com.cpu().numpy() != rcom).sum())},
+    }
+
+
 def load_traffic(workload: str):
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
@@ -208,6 +257,8 @@ def main():
     ap.add_argument("--workload", default="highload_b256")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--next-only", action="store_true",
+                    help="only the steps next to the attention path (commit step), as JSON; for profiling")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (torch copy kernel), the known-size "
                          "reference that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -221,6 +272,9 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     dev = "cuda:0"
+    if args.next_only:
+        print(json.dumps({"next_rows": {"commit_step": measure_commit(dev)}}))
+        return
     cfg, chunk = parse_workload(args.workload)
     w, runner, res = measure(cfg, chunk, args.steps, args.warmup, dev)
 
@@ -283,6 +337,7 @@ def main():
             del w2, r2
             torch.cuda.empty_cache()
         line["other_configs"] = others
+        line["next_rows"] = {"commit_step": measure_commit(dev)}
     line["paper_context"] = ("the paper reports no kernel-level number for this path; its system "
                              "results (A100-80GB, FP16) are not comparable")
     print(json.dumps(line))

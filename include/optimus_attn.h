@@ -164,6 +164,36 @@ int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable);
 int optimus_attn_timing_read(optimus_attn_plan_t* plan, float* total_ms_out,
                              int32_t* forwards_out);
 
+/* ---------------------------------------------------------------------------
+ * Commit step (Sec. 2.3, Sec. 4.1; threshold 0.9 in Sec. 7.1): every chunk
+ * position gets a confidence and the positions whose confidence exceeds the
+ * threshold are committed.  Reading: confidence = largest softmax probability
+ * of the position's logit row, token = first index attaining it.  With
+ * min_commit = 1 a request that has chunk tokens but none above the threshold
+ * commits its most confident one (first on ties), so decoding always advances.
+ * All pointers are device memory; nothing is allocated; asynchronous on the
+ * stream.                                                                      */
+typedef struct {
+  int32_t num_tokens;   /* T = rows of logits, <= 65535                          */
+  int32_t vocab;        /* V >= 1 used entries per row                           */
+  int64_t row_stride;   /* elements between rows: multiple of 8, >= V rounded up
+                           to a multiple of 8 (rows are read in 16-byte pieces)  */
+  float   threshold;    /* commit iff confidence > threshold                     */
+  int32_t batch;        /* requests described by cu_q; 0 = no per-request rule   */
+  int32_t min_commit;   /* 0 or 1                                                */
+  int32_t reserved0;
+} optimus_commit_params_t;
+
+/* Scratch bytes optimus_commit_forward needs for these parameters (0 on bad ones). */
+size_t optimus_commit_workspace_bytes(const optimus_commit_params_t* params);
+
+/* logits: bf16 [T, row_stride].  cu_q: int32 [batch+1] (ignored if batch == 0).
+ * token_out int32 [T], conf_out fp32 [T], commit_out int32 [T] (0/1).          */
+int optimus_commit_forward(const optimus_commit_params_t* params, int device, const void* logits,
+                           const int32_t* cu_q, int32_t* token_out, float* conf_out,
+                           int32_t* commit_out, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
 const char* optimus_status_string(int status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */
 const char* optimus_last_hip_error(void);

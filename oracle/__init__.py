@@ -19,15 +19,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle_attn.c")
+_SRCS = [_SRC, os.path.join(_HERE, "oracle_commit.c")]
 _LIB = os.path.join(_HERE, "liboracle_attn.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile ``oracle_attn.c`` with gcc into ``liboracle_attn.so`` (in place)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or \
+            os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               _SRC, "-o", _LIB, "-lm"]
+               *_SRCS, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -61,6 +63,7 @@ def _load():
                      "oracle_partial_row"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_merge_partials.restype = None
+        _lib.oracle_commit.restype = ctypes.c_int
     return _lib
 
 
@@ -200,3 +203,31 @@ def merge_partials(o_part: np.ndarray, m: np.ndarray, l: np.ndarray) -> np.ndarr
     lib.oracle_merge_partials(ctypes.c_int32(S), ctypes.c_int32(D), _f64(o_part), _f64(m), _f64(l),
                               _f64(o))
     return o
+
+
+def commit(logits_bits: np.ndarray, vocab: int, threshold: float, cu_q=None, min_commit: int = 0):
+    """Commit step on bf16 logits ``[T, row_stride]`` (uint16 bit patterns).
+
+    Returns ``(token int32 [T], confidence float64 [T], commit int32 [T])``.
+    """
+    lib = _load()
+    logits_bits = np.ascontiguousarray(logits_bits)
+    assert logits_bits.dtype == np.uint16 and logits_bits.ndim == 2
+    T, stride = logits_bits.shape
+    token = np.zeros(T, dtype=np.int32)
+    conf = np.zeros(T, dtype=np.float64)
+    com = np.zeros(T, dtype=np.int32)
+    if cu_q is None:
+        cu_p, batch = ctypes.POINTER(ctypes.c_int32)(), 0
+    else:
+        cu, cu_p = _i32(cu_q)
+        batch = len(cu) - 1
+    rc = lib.oracle_commit(ctypes.c_int32(T), ctypes.c_int32(vocab), ctypes.c_int64(stride),
+                           logits_bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)),
+                           ctypes.c_double(threshold), ctypes.c_int32(batch), cu_p,
+                           ctypes.c_int32(min_commit),
+                           token.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _f64(conf),
+                           com.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    if rc != 0:
+        raise ValueError("oracle_commit: bad argument")
+    return token, conf, com

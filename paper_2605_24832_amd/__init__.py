@@ -11,4 +11,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     status_string,
+    commit_params,
+    commit_workspace_bytes,
+    commit_forward,
 )

@@ -24,6 +24,7 @@ EXPORTS = (
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
     "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
     "optimus_status_string", "optimus_last_hip_error",
+    "optimus_commit_workspace_bytes", "optimus_commit_forward",
 )
 
 
@@ -46,6 +47,14 @@ class _CParams(ctypes.Structure):
         ("max_pages_per_req", ctypes.c_int32), ("reserved0", ctypes.c_int32),
         ("k_stride_page", ctypes.c_int64), ("k_stride_head", ctypes.c_int64),
         ("v_stride_page", ctypes.c_int64), ("v_stride_head", ctypes.c_int64),
+    ]
+
+
+class _CCommitParams(ctypes.Structure):
+    _fields_ = [
+        ("num_tokens", ctypes.c_int32), ("vocab", ctypes.c_int32), ("row_stride", ctypes.c_int64),
+        ("threshold", ctypes.c_float), ("batch", ctypes.c_int32), ("min_commit", ctypes.c_int32),
+        ("reserved0", ctypes.c_int32),
     ]
 
 
@@ -87,6 +96,10 @@ def load_library():
         lib.optimus_attn_set_timing.argtypes = [vp, i32]
         lib.optimus_attn_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float),
                                                  ctypes.POINTER(ctypes.c_int32)]
+        lib.optimus_commit_workspace_bytes.argtypes = [ctypes.POINTER(_CCommitParams)]
+        lib.optimus_commit_workspace_bytes.restype = ctypes.c_size_t
+        lib.optimus_commit_forward.argtypes = [ctypes.POINTER(_CCommitParams), ctypes.c_int, vp, vp,
+                                               vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.optimus_status_string.argtypes = [ctypes.c_int]
         lib.optimus_status_string.restype = ctypes.c_char_p
         lib.optimus_last_hip_error.argtypes = []
@@ -248,3 +261,25 @@ class Plan:
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_timing_read")
         return float(ms.value), int(n.value)
+
+
+def commit_params(num_tokens, vocab, row_stride, threshold=0.9, batch=0, min_commit=0) -> _CCommitParams:
+    c = _CCommitParams()
+    c.num_tokens, c.vocab, c.row_stride = int(num_tokens), int(vocab), int(row_stride)
+    c.threshold, c.batch, c.min_commit = float(threshold), int(batch), int(min_commit)
+    return c
+
+
+def commit_workspace_bytes(params: _CCommitParams) -> int:
+    return int(load_library().optimus_commit_workspace_bytes(ctypes.byref(params)))
+
+
+def commit_forward(params: _CCommitParams, logits, cu_q, token_out, conf_out, commit_out, workspace,
+                   device: int = 0, stream=None) -> None:
+    """optimus_commit_forward on torch device tensors (argument marshalling only)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load_library().optimus_commit_forward(
+        ctypes.byref(params), int(device), _ptr(logits), _ptr(cu_q), _ptr(token_out), _ptr(conf_out),
+        _ptr(commit_out), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
+    if rc != 0:
+        raise OptimusError(rc, "optimus_commit_forward")

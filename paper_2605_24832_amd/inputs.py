@@ -269,3 +269,26 @@ def make_config(k: int, *, device="cpu", chunk: int | None = None, scale_down: i
                              block_inner=np.zeros(R, dtype=np.int64), shuffle_pages=True,
                              peaked_frac=0.01, kv_layout=kv_layout, device=device)
     raise ValueError(f"config index {k} not in 0..4")
+
+
+def make_logits(num_tokens: int, vocab: int, *, seed: int, row_stride: int | None = None,
+                max_margin: float | None = None, device="cpu") -> torch.Tensor:
+    """bf16 logits ``[T, row_stride]`` for the commit step: N(0,1) noise plus, per row, one
+    winner raised by a margin drawn uniformly from [0, max_margin] (default ln V + 6: the
+    noise sums to about V * e^0.5, so the winner's probability sweeps 0..1), so that confidences
+    cover (0, 1) and a fair share exceeds the 0.9 threshold of the paper's setup.  Entries
+    beyond ``vocab`` (row padding) are NaN: they must never be looked at."""
+    device = torch.device(device)
+    stride = (vocab + 7) // 8 * 8 if row_stride is None else row_stride
+    if max_margin is None:
+        max_margin = float(np.log(vocab) + 6.0)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    x = torch.full((num_tokens, stride), float("nan"), dtype=torch.bfloat16, device=device)
+    x[:, :vocab] = _randn_bf16((num_tokens, vocab), gen, device)
+    rng = np.random.RandomState(seed)
+    win = torch.as_tensor(rng.randint(0, vocab, size=num_tokens), device=device)
+    margin = torch.as_tensor(rng.uniform(0.0, max_margin, size=num_tokens), device=device)
+    rows = torch.arange(num_tokens, device=device)
+    x[rows, win] = (x[rows, win].float() + margin.float()).to(torch.bfloat16)
+    return x

@@ -1,0 +1,73 @@
+"""Pins of the commit-step oracle (confidence = largest softmax probability, commit iff it
+exceeds the threshold) against a library routine, closed forms and invariants."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_24832_amd import inputs
+
+
+def bits(x):
+    return inputs.to_bits(x.to(torch.bfloat16))
+
+
+def test_matches_torch_softmax_fp64(oracle_mod):
+    x = inputs.make_logits(37, 1000, seed=1, row_stride=1008)
+    tok, conf, com = oracle_mod.commit(inputs.to_bits(x), 1000, 0.9)
+    p = torch.softmax(x[:, :1000].double(), dim=-1)
+    np.testing.assert_allclose(conf, p.max(dim=-1).values.numpy(), rtol=1e-13, atol=0)
+    np.testing.assert_array_equal(tok, p.argmax(dim=-1).numpy())
+    np.testing.assert_array_equal(com, (conf > np.float64(np.float32(0.9))).astype(np.int32))
+    assert 0 < com.sum() < len(com)  # the synthetic margins straddle the threshold
+    assert np.isfinite(conf).all()   # the NaN padding beyond the vocabulary is never read
+
+
+def test_two_logits_closed_form_is_a_sigmoid(oracle_mod):
+    a = torch.tensor([[1.5, -0.25], [0.0, 0.0], [-3.0, 2.0]])
+    tok, conf, _ = oracle_mod.commit(bits(torch.cat([a, torch.zeros(3, 6)], 1)), 2, 0.5)
+    d = (a[:, 0] - a[:, 1]).abs().double().numpy()
+    np.testing.assert_allclose(conf, 1.0 / (1.0 + np.exp(-d)), rtol=1e-15)
+    np.testing.assert_array_equal(tok, [0, 0, 1])  # a tie goes to the first index
+
+
+def test_uniform_row_and_shift_invariance(oracle_mod):
+    V = 24
+    u = torch.full((1, V), 0.75)
+    tok, conf, com = oracle_mod.commit(bits(u), V, 0.9)
+    assert tok[0] == 0 and abs(conf[0] - 1.0 / V) < 1e-16 and com[0] == 0
+    # values on a 1/8 grid stay exact in bf16 after adding 2.0
+    x = (torch.round(torch.randn(5, V) * 8) / 8).clamp(-3, 3)
+    a = oracle_mod.commit(bits(x), V, 0.3)
+    b = oracle_mod.commit(bits(x + 2.0), V, 0.3)
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-14)
+
+
+def test_peaked_row_is_committed_and_threshold_is_strict(oracle_mod):
+    V = 16
+    x = torch.zeros(2, V)
+    x[0, 5] = 40.0                       # confidence 1 to 1e-16
+    x[1, :2] = torch.tensor([0.0, 0.0])  # all equal: 1/16 = 0.0625 exactly
+    tok, conf, com = oracle_mod.commit(bits(x), V, 0.0625)
+    assert tok[0] == 5 and conf[0] > 1 - 1e-12 and com[0] == 1
+    assert conf[1] == 0.0625 and com[1] == 0      # "exceeds": equality does not commit
+    _, _, com2 = oracle_mod.commit(bits(x), V, 0.0624)
+    assert com2[1] == 1
+
+
+def test_progress_rule_commits_the_most_confident_token(oracle_mod):
+    V = 32
+    g = torch.Generator().manual_seed(3)
+    x = torch.randn(9, V, generator=g)          # flat rows: nothing near 0.9
+    x[4, 7] += 30.0                             # one sure token in request 1
+    cu = [0, 3, 6, 6, 9]                        # request 2 is empty
+    tok, conf, com = oracle_mod.commit(bits(x), V, 0.9, cu, 1)
+    assert com[4] == 1 and com[3] == 0 and com[5] == 0       # request 1: its own commit suffices
+    for lo, hi in ((0, 3), (6, 9)):
+        assert com[lo:hi].sum() == 1 and com[lo + int(np.argmax(conf[lo:hi]))] == 1
+    _, _, com0 = oracle_mod.commit(bits(x), V, 0.9, cu, 0)
+    assert com0.sum() == 1 and com0[4] == 1
+    # ties inside a request: the first one is forced
+    y = torch.zeros(4, V)
+    _, _, com3 = oracle_mod.commit(bits(y), V, 0.9, [0, 4], 1)
+    np.testing.assert_array_equal(com3, [1, 0, 0, 0])
