@@ -239,6 +239,120 @@ def measure_commit(device: str, steps: int = 20):
     }
 
 
+def measure_reorg(device: str, steps: int = 50):
+    """The step-wise reorganisation on the decode state of the default workload's batch: 256
+    requests in blocks of 32.  Two tiny integer kernels: the time is launch latency."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2605_24832_amd import inputs, reorg_forward
+    R, B = 256, 32
+    dec, s, want = inputs.make_decode_state(R, B, seed=inputs.BASE_SEED + 50, chunk_choices=(1, 2, 4))
+    t = lambda a, dt: torch.as_tensor(a, dtype=dt, device=device)
+    d_dec, d_s, d_w = t(dec, torch.uint8), t(s, torch.int32), t(want, torch.int32)
+    mk = lambda n: torch.empty(n, dtype=torch.int32, device=device)
+    chunk, cu, L = mk(R), mk(R + 1), mk(R)
+    cap = int(want.sum())
+    pos, slot, req = mk(cap), mk(cap), mk(cap)
+    call = lambda: reorg_forward(d_dec, d_s, d_w, chunk, cu, L, pos, slot, req)
+    call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    t0 = time.perf_counter()
+    ref = oracle.reorganise(dec, s, want)
+    cpu_s = time.perf_counter() - t0
+    n = int(cu[-1])
+    got = dict(chunk=chunk, cu_q=cu, prefix_len=L, q_pos=pos[:n], kv_slot=slot[:n], token_req=req[:n])
+    same = all(np.array_equal(got[k].cpu().numpy(), ref[k]) for k in ref)
+    return {"workload": f"step-wise reorganisation: {R} requests, block {B}, chunk in (1,2,4)",
+            "ms_per_step": ms, "requests_per_s": R / (ms * 1e-3), "chunk_tokens": n,
+            "cpu_oracle": {"value": R / cpu_s, "unit": "requests/s", "cores": 1},
+            "parity_vs_oracle": {"identical": bool(same)}}
+
+
+def measure_selector(device: str):
+    """Chunk-size selection (Sec. 5) fed by this machine's own profile: one decoder layer's step
+    latency over batch x chunk = the attention step of this library (prefix 1024 per request,
+    32/8 heads of 128) plus the layer's four FC products as plain library GEMMs (an 8B model's
+    shapes: hidden 4096, qkv 6144, gate+up 24576, down 12288 -> 4096), fitted with the
+    three-regime model and used to pick the chunk size per batch size for a synthetic
+    committed-tokens table with diminishing returns."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2605_24832_amd import inputs, latency_eval, latency_fit, select_chunk
+    hidden, qkv, ffn = 4096, 6144, 12288
+    gen = torch.Generator(device=device)
+    gen.manual_seed(inputs.BASE_SEED + 60)
+    wts = [torch.randn(hidden, n, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16) * 0.02
+           for n in (qkv, hidden, 2 * ffn)] + \
+          [torch.randn(ffn, hidden, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16) * 0.02]
+
+    def fc_ms_once(x_tokens: int, reps: int = 20):
+        a = torch.randn(x_tokens, hidden, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+        a2 = torch.randn(x_tokens, ffn, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+        def layer():
+            a @ wts[0]; a @ wts[1]; a @ wts[2]; a2 @ wts[3]
+        for _ in range(3):
+            layer()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            layer()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    samples = []
+    fc_cache = {}
+    for b in (1, 4, 16, 64, 256):
+        for c in (1, 2, 4, 8, 16, 32):
+            w = inputs.make_workload(f"sel_b{b}_c{c}", seed=inputs.BASE_SEED + 61, num_q_heads=32,
+                                     num_kv_heads=8, head_dim=128, page_size=16, block_size=32,
+                                     prefix_len=[1024] * b, chunk=[c] * b, poison=False, device=device)
+            r = Runner(w, copies=1)
+            attn_ms = min(r.timed(10, 3)[0] for _ in range(3))   # wall clock: keep the quietest of three
+            x = b * c
+            if x not in fc_cache:
+                fc_cache[x] = min(fc_ms_once(x) for _ in range(3))
+            samples.append((x, b, c, attn_ms, fc_cache[x]))
+            del r, w
+    xs = np.array([s[0] for s in samples], dtype=np.float64)
+    ts = np.array([s[3] + s[4] for s in samples], dtype=np.float64)
+    model, sse = latency_fit(xs, ts)
+    ref = oracle.selector.latency_fit(xs, ts)
+    pred = np.array([latency_eval(model, x) for x in xs])
+    cs = [2, 4, 8, 16, 32]
+    # committed tokens per request and step: synthetic, rising with diminishing returns (Fig. 5(b) shape)
+    n_commit = [1.0 + 2.4 * (1.0 - float(np.exp(-c / 10.0))) for c in cs]
+    picks = {}
+    agree = True
+    for b in (1, 4, 16, 64, 256, 1024):
+        i, rates = select_chunk(model, b, cs, n_commit)
+        j, _ = oracle.selector.select_chunk(ref, b, cs, n_commit)
+        agree &= i == j
+        picks[str(b)] = cs[i]
+    return {"workload": "layer latency over batch x chunk: attention step (prefix 1024, 32/8 heads x 128) + "
+                        "4 FC GEMMs of an 8B model's layer; 30 (batch, chunk) samples",
+            "model": {"x_break": list(model.x_break), "beta1_ms_per_token": list(model.beta1),
+                      "beta0_ms": list(model.beta0)},
+            "fit_rel_err_mean": float(np.mean(np.abs(pred - ts) / ts)),
+            "fit_rel_err_max": float(np.max(np.abs(pred - ts) / ts)),
+            "n_commit_table": dict(zip(map(str, cs), n_commit)),
+            "chunk_selected_per_batch": picks,
+            "parity_vs_oracle": {"sse_rel_diff": abs(sse - ref["sse"]) / ref["sse"], "same_choices": bool(agree)},
+            "samples_ms": [[int(s[0]), int(s[1]), int(s[2]), round(s[3], 4), round(s[4], 4)] for s in samples]}
+
+
 def load_traffic(workload: str):
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
@@ -273,7 +387,9 @@ def main():
         raise SystemExit("bench.py needs a GPU")
     dev = "cuda:0"
     if args.next_only:
-        print(json.dumps({"next_rows": {"commit_step": measure_commit(dev)}}))
+        print(json.dumps({"next_rows": {"commit_step": measure_commit(dev),
+                                        "reorg_step": measure_reorg(dev),
+                                        "chunk_selector": measure_selector(dev)}}))
         return
     cfg, chunk = parse_workload(args.workload)
     w, runner, res = measure(cfg, chunk, args.steps, args.warmup, dev)
@@ -337,7 +453,8 @@ def main():
             del w2, r2
             torch.cuda.empty_cache()
         line["other_configs"] = others
-        line["next_rows"] = {"commit_step": measure_commit(dev)}
+        line["next_rows"] = {"commit_step": measure_commit(dev), "reorg_step": measure_reorg(dev),
+                             "chunk_selector": measure_selector(dev)}
     line["paper_context"] = ("the paper reports no kernel-level number for this path; its system "
                              "results (A100-80GB, FP16) are not comparable")
     print(json.dumps(line))

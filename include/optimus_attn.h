@@ -194,6 +194,62 @@ int optimus_commit_forward(const optimus_commit_params_t* params, int device, co
                            int32_t* commit_out, void* workspace, size_t workspace_bytes,
                            void* hip_stream);
 
+/* ---------------------------------------------------------------------------
+ * Step-wise reorganisation (Sec. 4.4): rebuild every request's chunk for this
+ * step from the tokens decoded so far.  Reading: the chunk is the first
+ * min(chunk_req_i, undecoded_i) not yet decoded positions of the current block
+ * (in-block streaming, Sec. 7.2), in sequence order; the decoded positions of
+ * the block are cached, so the cached length is block_start_i + decoded_i and
+ * chunk token j uses KV slot cached length + j.
+ * All pointers are device memory; nothing is allocated; asynchronous.
+ *   decoded       uint8 [batch, block_size], non-zero = decoded
+ *   block_start   int32 [batch]  sequence position of the block's first token
+ *   chunk_req     int32 [batch]  chunk size asked for (negative counts as 0)
+ *   chunk_out     int32 [batch]; cu_q_out int32 [batch+1]; prefix_len_out int32 [batch]
+ *   q_pos_out, kv_slot_out, token_req_out  int32 [>= sum of chunk_out] (at most
+ *       sum of min(chunk_req, block_size)): sequence position, KV slot and
+ *       request of every chunk token, ordered by request then position.       */
+int optimus_reorg_forward(int device, int32_t batch, int32_t block_size, const uint8_t* decoded,
+                          const int32_t* block_start, const int32_t* chunk_req,
+                          int32_t* chunk_out, int32_t* cu_q_out, int32_t* prefix_len_out,
+                          int32_t* q_pos_out, int32_t* kv_slot_out, int32_t* token_req_out,
+                          void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Saturation-aware chunk-size selection (Sec. 5).  Host memory only, no GPU.
+ *
+ * Latency model (Sec. 5.2): three affine regimes over the step's token count
+ * x = batch * chunk: memory-bound, transition, compute-bound.
+ *   T(x) = beta1[k] * x + beta0[k],  k = 0 if x < x_break[0], 1 if x < x_break[1], else 2. */
+typedef struct optimus_latency_model {
+  double x_break[2];
+  double beta1[3];
+  double beta0[3];
+} optimus_latency_model_t;
+
+/* Fit the model to profiled samples (x_i, latency_i), 6 <= num_samples <= 2048, in any order.
+ * Reading (the paper says only that the coefficients come from offline profiling): samples are
+ * ordered by x, cut into three runs, each run gets its own least-squares line, and the two cuts
+ * are the pair that minimises the total squared error (first such pair in (cut0, cut1) order);
+ * a cut never separates equal x and every run needs two distinct x.  x_break is the midpoint
+ * of the two samples a cut separates.  sse_out (may be NULL) receives the total squared error.
+ * Returns OPTIMUS_ERR_INVALID_ARGUMENT for null pointers, non-finite or negative samples, or
+ * when no admissible pair of cuts exists.                                                   */
+int optimus_latency_fit(int32_t num_samples, const double* x, const double* latency,
+                        optimus_latency_model_t* model_out, double* sse_out);
+/* T(x) of the model (NaN for a null model). */
+double optimus_latency_eval(const optimus_latency_model_t* model, double x);
+
+/* Sec. 5.1: best_index_out = argmax_i n_commit[i] * batch / T(batch * chunk_sizes[i]) over the
+ * num_candidates candidate chunk sizes (first index on ties); n_commit[i] is the caller's
+ * estimate of tokens committed per request and step at chunk_sizes[i] (Sec. 5.3).  rate_out
+ * (may be NULL) receives the num_candidates objective values (tokens per latency unit).
+ * Returns OPTIMUS_ERR_INVALID_ARGUMENT for null pointers, batch < 1, a chunk size < 1, a
+ * negative or NaN n_commit, or a model latency that is not positive at a candidate.          */
+int optimus_select_chunk(const optimus_latency_model_t* model, int32_t batch,
+                         int32_t num_candidates, const int32_t* chunk_sizes,
+                         const double* n_commit, int32_t* best_index_out, double* rate_out);
+
 const char* optimus_status_string(int status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */
 const char* optimus_last_hip_error(void);

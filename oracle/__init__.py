@@ -231,3 +231,7 @@ def commit(logits_bits: np.ndarray, vocab: int, threshold: float, cu_q=None, min
     if rc != 0:
         raise ValueError("oracle_commit: bad argument")
     return token, conf, com
+
+
+from .oracle_reorg import reorganise  # noqa: E402,F401  (step-wise reorganisation, Sec. 4.4)
+from . import oracle_selector as selector  # noqa: E402,F401  (chunk-size selection, Sec. 5)

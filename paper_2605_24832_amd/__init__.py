@@ -14,4 +14,9 @@ from .binding import (  # noqa: F401
     commit_params,
     commit_workspace_bytes,
     commit_forward,
+    reorg_forward,
+    LatencyModel,
+    latency_fit,
+    latency_eval,
+    select_chunk,
 )

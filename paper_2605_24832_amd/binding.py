@@ -24,7 +24,8 @@ EXPORTS = (
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
     "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
     "optimus_status_string", "optimus_last_hip_error",
-    "optimus_commit_workspace_bytes", "optimus_commit_forward",
+    "optimus_commit_workspace_bytes", "optimus_commit_forward", "optimus_reorg_forward",
+    "optimus_latency_fit", "optimus_latency_eval", "optimus_select_chunk",
 )
 
 
@@ -68,6 +69,12 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+class LatencyModel(ctypes.Structure):
+    """optimus_latency_model_t: three affine regimes over x = batch * chunk."""
+    _fields_ = [("x_break", ctypes.c_double * 2), ("beta1", ctypes.c_double * 3),
+                ("beta0", ctypes.c_double * 3)]
+
+
 def load_library():
     """Load the HIP library (once).  Raises if it has not been built."""
     global _lib
@@ -100,6 +107,13 @@ def load_library():
         lib.optimus_commit_workspace_bytes.restype = ctypes.c_size_t
         lib.optimus_commit_forward.argtypes = [ctypes.POINTER(_CCommitParams), ctypes.c_int, vp, vp,
                                                vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.optimus_reorg_forward.argtypes = [ctypes.c_int, i32, i32] + [vp] * 10
+        dp = ctypes.POINTER(ctypes.c_double)
+        mp = ctypes.POINTER(LatencyModel)
+        lib.optimus_latency_fit.argtypes = [i32, dp, dp, mp, dp]
+        lib.optimus_latency_eval.argtypes = [mp, ctypes.c_double]
+        lib.optimus_latency_eval.restype = ctypes.c_double
+        lib.optimus_select_chunk.argtypes = [mp, i32, i32, ctypes.POINTER(i32), dp, ctypes.POINTER(i32), dp]
         lib.optimus_status_string.argtypes = [ctypes.c_int]
         lib.optimus_status_string.restype = ctypes.c_char_p
         lib.optimus_last_hip_error.argtypes = []
@@ -283,3 +297,53 @@ def commit_forward(params: _CCommitParams, logits, cu_q, token_out, conf_out, co
         _ptr(commit_out), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
     if rc != 0:
         raise OptimusError(rc, "optimus_commit_forward")
+
+
+def reorg_forward(decoded, block_start, chunk_req, chunk_out, cu_q_out, prefix_len_out, q_pos_out,
+                  kv_slot_out, token_req_out, device: int = 0, stream=None) -> None:
+    """optimus_reorg_forward on torch device tensors (argument marshalling only)."""
+    batch, block_size = decoded.shape
+    rc = load_library().optimus_reorg_forward(
+        int(device), int(batch), int(block_size), _ptr(decoded), _ptr(block_start), _ptr(chunk_req),
+        _ptr(chunk_out), _ptr(cu_q_out), _ptr(prefix_len_out), _ptr(q_pos_out), _ptr(kv_slot_out),
+        _ptr(token_req_out), _stream_ptr(stream))
+    if rc != 0:
+        raise OptimusError(rc, "optimus_reorg_forward")
+
+
+def _dbl(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def latency_fit(x, latency):
+    """optimus_latency_fit on host arrays: returns ``(LatencyModel, sse)``."""
+    xa, xp = _dbl(x)
+    ta, tp = _dbl(latency)
+    if xa.shape != ta.shape or xa.ndim != 1:
+        raise ValueError("x and latency must be 1-d arrays of one length")
+    m, sse = LatencyModel(), ctypes.c_double()
+    rc = load_library().optimus_latency_fit(len(xa), xp, tp, ctypes.byref(m), ctypes.byref(sse))
+    if rc != 0:
+        raise OptimusError(rc, "optimus_latency_fit")
+    return m, sse.value
+
+
+def latency_eval(model: LatencyModel, x: float) -> float:
+    return float(load_library().optimus_latency_eval(ctypes.byref(model), float(x)))
+
+
+def select_chunk(model: LatencyModel, batch: int, chunk_sizes, n_commit):
+    """optimus_select_chunk: returns ``(best_index, rates float64 [num_candidates])``."""
+    cs = np.ascontiguousarray(chunk_sizes, dtype=np.int32)
+    na, np_ = _dbl(n_commit)
+    if cs.shape != na.shape or cs.ndim != 1:
+        raise ValueError("chunk_sizes and n_commit must be 1-d arrays of one length")
+    rates = np.zeros(len(cs), dtype=np.float64)
+    best = ctypes.c_int32(-1)
+    rc = load_library().optimus_select_chunk(
+        ctypes.byref(model), int(batch), len(cs), cs.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+        np_, ctypes.byref(best), rates.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if rc != 0:
+        raise OptimusError(rc, "optimus_select_chunk")
+    return int(best.value), rates

@@ -292,3 +292,20 @@ def make_logits(num_tokens: int, vocab: int, *, seed: int, row_stride: int | Non
     rows = torch.arange(num_tokens, device=device)
     x[rows, win] = (x[rows, win].float() + margin.float()).to(torch.bfloat16)
     return x
+
+
+def make_decode_state(batch: int, block_size: int, *, seed: int, decoded_fraction=None,
+                      chunk_choices=(1, 2, 4, 8, 16, 32), max_context: int = 8192):
+    """Decode state of ``batch`` requests in the middle of a block, for the step-wise
+    reorganisation: a uint8 ``[batch, block_size]`` decoded map (every request draws its own
+    decoded fraction from [0, 1] unless one is given; confident positions are decoded out of
+    order, so the map has holes), the block's start position (a multiple of the block size) and
+    the chunk size asked for.  Returns numpy arrays ``(decoded, block_start, chunk_req)``."""
+    rng = np.random.RandomState(seed)
+    frac = rng.uniform(0.0, 1.0, size=batch) if decoded_fraction is None else \
+        np.full(batch, float(decoded_fraction))
+    decoded = (rng.uniform(size=(batch, block_size)) < frac[:, None]).astype(np.uint8)
+    blocks = max(1, max_context // block_size)
+    block_start = (rng.randint(0, blocks, size=batch) * block_size).astype(np.int32)
+    chunk_req = rng.choice(list(chunk_choices), size=batch).astype(np.int32)
+    return decoded, block_start, chunk_req
