@@ -191,7 +191,7 @@ def cpu_baseline(w, runner, budget_s: float = 15.0):
 
 
 def measure_commit(device: str, steps: int = 20):
-    """The commit step on the chunk tokens of the default workload: 604 rows
+    """The commit step (Sec. 2.3) on the chunk tokens of the default workload: 604 rows
     of a 151936-entry bf16 vocabulary.  HBM-bound scan: algorithmic bytes = T * V * 2."""
     import numpy as np
     import torch
