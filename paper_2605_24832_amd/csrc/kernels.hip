@@ -692,20 +692,356 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   }
 }
 
-// One launch serves every kind of work item: the block looks at its item's row count and
-// runs the matching body, so that a ragged batch (chunk sizes 1..32 side by side) is one
-// grid in costliest-first order instead of one small grid per kind.  All bodies fit two
-// waves per SIMD; wider items (4 subtiles per wave, one wave per SIMD) were measured slower
-// per flop than two 128-row items that share their K/V stream through the caches.
+// ---------------------------------------------------------------------------
+// attention kernel for the widest row tiles ("wide" body): 65..128 query rows.
+// Each wave owns 32 rows and both products use the 32x32x16 bf16 MFMA, whose
+// register layout (lane = 32*h + r, r 0..31, h 0..1) is
+//   A: row r, k = 8h..8h+7     B: col r, k = 8h..8h+7
+//   C/D: 16 floats, col r, register v -> row 8*(v/4) + 4h + v%4
+// so a lane holds 16 scores of ONE query row per tile: the row maximum crosses
+// lanes once, the per-row softmax bookkeeping is paid once per 16 scores, and
+// the row sum is a packed bf16 dot product with ones (it adds up exactly the
+// rounded P that enters the second product).
+// K/V tiles reach LDS without passing through registers (global_load_lds, 16
+// bytes per lane; lane i of an instruction writes piece base+i, so the LDS
+// layout is produced by choosing which global piece each lane fetches), in a
+// ring of kWideStages tiles that is filled three tiles ahead.  The loop is
+// software-pipelined: the score product of tile t+1 is issued before the
+// softmax of tile t, so MFMA and VALU work of one wave overlap; the waits on
+// the load counter are written by hand (the ring is only correct because each
+// wave issues exactly 2*LPT loads per tile and nothing else in the loop).
+// LDS layouts (16-byte pieces):
+//   K: piece 32*g + i holds d group g (8 values) of the key whose score lands in
+//      row i of S^T; row i is key (i with bits 2 and 3 swapped), which makes the
+//      8 scores a lane packs for one PV product 8 consecutive keys.  The operand
+//      of step s is piece 64*s + lane: a contiguous read.
+//   V: piece 4*d + (o ^ ((d >> 2) & 3)) holds keys 8o..8o+7 of row d; the XOR
+//      spreads the 16 lanes one LDS cycle serves over all banks.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+constexpr int kWideStages = 4;
+
+template <int D>
+constexpr int wide_smem_floats() { return kWideStages * 2 * (D * 4) * 4; }
+
+// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, the other counters left at "no wait").
+#define OPT_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+// Workgroup barrier without a memory fence (a fence would wait for every load in flight);
+// the empty asm statements keep the compiler from moving LDS accesses across it.
+#define OPT_BARRIER_NO_FENCE()          \
+  do {                                  \
+    asm volatile("" ::: "memory");      \
+    __builtin_amdgcn_s_barrier();       \
+    asm volatile("" ::: "memory");      \
+  } while (0)
+
+// 16 bytes per lane from global memory straight into LDS: lane i writes lds_addr + 16*i.
+// Written as inline asm on purpose: when the compiler sees this instruction it makes every
+// memory-counter wait it inserts anywhere in the kernel a wait for all loads, which would undo
+// the prefetch of the other bodies.  The compiler therefore does not count these loads; the
+// body below waits for them by hand, and a compiler-inserted wait for one of its own loads
+// only waits longer than needed (the counter retires in order).  M0 holds the LDS address
+// (one wait state between the scalar write of M0 and its use).
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int D, int LGP>
+__device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimus_work_item_t& it,
+                                               float* smem) {
+  constexpr int KS = D / 16, DB = D / 32, P = 1 << LGP;
+  constexpr int PIECES = D * 4;        // 16-byte pieces of a K (= of a V) tile
+  constexpr int LPT = PIECES / 256;    // load instructions per wave per tensor per tile
+  constexpr int S = kWideStages, STAGE = 2 * PIECES;
+  u32x4* sm = reinterpret_cast<u32x4*>(smem);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r32 = lane & 31, h = lane >> 5;
+  const int G = a.group;
+
+  const int rl = wave * 32 + r32;
+  const bool valid = rl < it.row_count;
+  const int row = it.row_begin + (valid ? rl : 0);
+  const int jq = row / G, uq = row - jq * G;
+  const int64_t row_off = ((int64_t)(it.q_token0 + jq) * a.num_q_heads + it.kv_head * G + uq) * D;
+  bf16x8 qreg[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    u32x4 x = *reinterpret_cast<const u32x4*>(a.q + row_off + s * 16 + h * 8);
+    if (!valid) x = u32x4{0u, 0u, 0u, 0u};
+    qreg[s] = __builtin_bit_cast(bf16x8, x);
+  }
+  const int L = a.prefix_len[it.req];
+  const int d_in = L - a.block_start[it.req];
+  const int vis_end = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + jq) / a.block_size + 1) * a.block_size - d_in;
+  const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
+  const int mask_from = min(it.kv_end, vis_min);
+  const int lim = min(it.kv_end, vis_end);
+  const bool wave_has_rows = wave * 32 < it.row_count;  // uniform per wave
+
+  float m = -INFINITY, lsum = 0.f;
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+
+  const int32_t* bt = a.block_table + (int64_t)it.req * a.max_pages_per_req;
+  const int last_page = (it.kv_end - 1) >> LGP;
+  const char* kbase = reinterpret_cast<const char*>(a.k_pool + (int64_t)it.kv_head * a.k_stride_head);
+  const char* vbase = reinterpret_cast<const char*>(a.v_pool + (int64_t)it.kv_head * a.v_stride_head);
+  const int64_t kspb = a.k_stride_page * 2, vspb = a.v_stride_page * 2;
+  const float sc = a.scale_log2;
+  const int tile_lo = it.kv_begin / kTileTokens;
+  const int n = (it.kv_end + kTileTokens - 1) / kTileTokens - tile_lo;
+
+  // which global piece this lane fetches for LDS piece e = (4*i + wave)*64 + lane
+  uint32_t ksrc[LPT], vsrc[LPT];
+  bool second_page[LPT][2];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    const int e = (4 * i + wave) * 64 + lane;
+    const int g8 = e >> 5, pos = e & 31;
+    const int key = (pos & 19) | ((pos & 4) << 1) | ((pos & 8) >> 1);
+    const int d = e >> 2, o = (e & 3) ^ ((d >> 2) & 3);
+    if constexpr (LGP == 4) {
+      ksrc[i] = (uint32_t)(g8 * 16 + (key & 15)) * 16u;
+      vsrc[i] = (uint32_t)(d * 16 + 8 * (o & 1)) * 2u;
+      second_page[i][0] = key >= 16;
+      second_page[i][1] = o >= 2;
+    } else {
+      ksrc[i] = (uint32_t)(g8 * P + key) * 16u;
+      vsrc[i] = (uint32_t)(d * P + 8 * o) * 2u;
+      second_page[i][0] = second_page[i][1] = false;
+    }
+  }
+  // Page ids live in a register, lane i holding the id of page page_base + i, and reach the
+  // scalar unit through v_readlane: no memory access per tile (a load inside the loop would
+  // make every wait for it drain the tile loads in flight).  Refilled every 64 pages.
+  int page_base = 0, page_reg = 0;
+  auto REFILL = [&](int first_page) {
+    page_base = first_page;
+    page_reg = bt[min(first_page + lane, last_page)];
+    // consume the value here, so that the wait for this load sits inside the (rare) refill
+    // path instead of at the join, where it would be taken on every tile
+    asm volatile("" : "+v"(page_reg));
+  };
+  REFILL((tile_lo * kTileTokens) >> LGP);
+  // item tile t -> ring stage t % S (K pieces first, then V), straight from global memory
+  auto ISSUE = [&](int t) {
+    const int tile = tile_lo + t;
+    const int pi0 = (tile * kTileTokens) >> LGP;
+    const int pi1 = LGP == 4 ? min(pi0 + 1, last_page) : pi0;   // clamped: its keys are masked
+    if (pi1 - page_base >= 64) REFILL(pi0);
+    const int32_t p0 = __builtin_amdgcn_readlane(page_reg, pi0 - page_base);
+    const int32_t p1 = LGP == 4 ? __builtin_amdgcn_readlane(page_reg, pi1 - page_base) : p0;
+    // low 32 bits of a generic pointer into LDS = the LDS byte address
+    const uint32_t dst = (uint32_t)(uintptr_t)(sm + (t & (S - 1)) * STAGE + wave * 64);
+    const uint32_t slot0 = LGP == 4 ? 0u : (uint32_t)((tile * kTileTokens) & (P - 1));
+    const char* k0 = kbase + (int64_t)p0 * kspb + slot0 * 16u;
+    const char* k1 = kbase + (int64_t)p1 * kspb;
+    const char* v0 = vbase + (int64_t)p0 * vspb + slot0 * 2u;
+    const char* v1 = vbase + (int64_t)p1 * vspb;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i)
+      load_to_lds_16((second_page[i][0] ? k1 : k0) + ksrc[i], dst + 16u * (256 * i));
+#pragma unroll
+    for (int i = 0; i < LPT; ++i)
+      load_to_lds_16((second_page[i][1] ? v1 : v0) + vsrc[i], dst + 16u * (PIECES + 256 * i));
+  };
+  // S^T of item tile t: register v of a lane is key 32*tile + 16*(v/8) + 8h + v%8, row r32
+  auto QK = [&](int t, f32x16& s) {
+    const u32x4* kb = sm + (t & (S - 1)) * STAGE + lane;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int st = 0; st < KS; ++st)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb[64 * st]), qreg[st], s, 0, 0, 0);
+  };
+  // running maximum after the scores of tile t: returns the reference value the tile's
+  // exponentials use and the factor the accumulators have to be scaled by before its PV
+  auto STATS = [&](int t, f32x16& s, bool masked, float& m_use, float& alpha) {
+    if (masked) {
+      const int key0 = (tile_lo + t) * kTileTokens + 8 * h;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = key0 + 16 * (v / 8) + (v % 8) < lim ? s[v] : -INFINITY;
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+    {
+      float x, y;
+      swap32(mx, x, y);
+      mx = fmaxf(x, y);
+    }
+    const float m_cand = fmaxf(m, mx * sc);
+    const float m_new = (m_cand - m > kMaxSlack) ? m_cand : m;   // lazy: see compute_tile
+    m_use = m_new == -INFINITY ? 0.f : m_new;
+    alpha = fast_exp2(m - m_use);
+    m = m_new;
+  };
+  auto SOFTMAX_PV = [&](int t, const f32x16& s, float m_use, bool masked) {
+    bf16x8 pt[2];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) pt[v / 8][v % 8] = (__bf16)fast_exp2(fmaf(s[v], sc, -m_use));
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+      const bf16x2 pr = {pt[v / 8][v % 8], pt[v / 8][v % 8 + 1]};
+      lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
+    }
+    const u32x4* vb = sm + (t & (S - 1)) * STAGE + PIECES;
+    const int key0 = (tile_lo + t) * kTileTokens + 8 * h;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int aa = 0; aa < 2; ++aa) {
+        const int d = 32 * db + r32, o = 2 * aa + h;
+        u32x4 vv = vb[4 * d + (o ^ ((d >> 2) & 3))];
+        if (masked) {   // keys at or beyond kv_end may hold anything: zero them
+          const int cnt = it.kv_end - (key0 + 16 * aa);
+          vv.x &= keep_mask(cnt); vv.y &= keep_mask(cnt - 2);
+          vv.z &= keep_mask(cnt - 4); vv.w &= keep_mask(cnt - 6);
+        }
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pt[aa], acc[db], 0, 0, 0);
+      }
+    }
+  };
+  auto RESCALE = [&](float alpha) {
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: some row moved its m
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] *= alpha;
+      lsum *= alpha;
+    }
+  };
+  auto tile_masked = [&](int t) { return (tile_lo + t + 1) * kTileTokens > mask_from; };
+
+  // ---- prologue: three tiles in flight, scores of tile 0
+#pragma unroll
+  for (int t0 = 0; t0 < S - 1; ++t0)
+    if (t0 < n) ISSUE(t0);
+  // tile 0 and the K half of tile 1 must have landed (see STEP below)
+  if (n >= 3) OPT_WAIT_VMCNT(3 * LPT);
+  else if (n == 2) OPT_WAIT_VMCNT(LPT);
+  else OPT_WAIT_VMCNT(0);
+  OPT_BARRIER_NO_FENCE();
+  f32x16 sa, sb;
+  float mu_a = 0.f, mu_b = 0.f, alpha = 1.f;
+  if (wave_has_rows) {
+    QK(0, sa);
+    STATS(0, sa, tile_masked(0), mu_a, alpha);   // accumulators are still zero: no rescale
+  }
+
+  // One pipelined step: loads of tile t+3, scores of tile t+1, softmax and PV of tile t.
+  // At its end tile t+1 (V) and tile t+2 (K) must have landed: all but the 2*LPT loads of
+  // tile t+3 and the LPT V loads of tile t+2 (K is issued before V).
+  auto STEP = [&](int t, f32x16& cur, float mu_cur, f32x16& nxt, float& mu_nxt) {
+    ISSUE(t + 3);
+    if (wave_has_rows) {
+      QK(t + 1, nxt);
+      SOFTMAX_PV(t, cur, mu_cur, false);
+      STATS(t + 1, nxt, false, mu_nxt, alpha);
+    }
+    OPT_WAIT_VMCNT(3 * LPT);
+    OPT_BARRIER_NO_FENCE();
+    if (wave_has_rows) RESCALE(alpha);
+  };
+  int t = 0;
+  const int n_plain = min(n, (mask_from - tile_lo * kTileTokens) / kTileTokens);  // leading unmasked tiles
+  for (; t + 4 < n && t + 2 < n_plain; t += 2) {
+    STEP(t, sa, mu_a, sb, mu_b);
+    STEP(t + 1, sb, mu_b, sa, mu_a);
+  }
+  // ---- remaining tiles: same step with every condition checked.  Once nothing is issued any
+  // more, what may still be in flight shrinks: with tile t+2 the last one only its V loads,
+  // after that nothing.
+  for (; t < n; ++t) {
+    const bool has_next = t + 1 < n, issue = t + 3 < n;
+    if (issue) ISSUE(t + 3);
+    if (wave_has_rows) {
+      if (has_next) QK(t + 1, sb);
+      SOFTMAX_PV(t, sa, mu_a, tile_masked(t));
+      if (has_next) STATS(t + 1, sb, tile_masked(t + 1), mu_b, alpha);
+    }
+    if (issue) OPT_WAIT_VMCNT(3 * LPT);
+    else if (t + 3 == n) OPT_WAIT_VMCNT(LPT);
+    else OPT_WAIT_VMCNT(0);
+    OPT_BARRIER_NO_FENCE();
+    if (wave_has_rows && has_next) {
+      RESCALE(alpha);
+      sa = sb;
+      mu_a = mu_b;
+    }
+  }
+
+  if (!valid) return;
+  {
+    float x, y;
+    swap32(lsum, x, y);
+    lsum = x + y;
+  }
+  if (it.part_row >= 0) {
+    float* po = a.ws_o + (int64_t)(it.part_row + rl) * D + 4 * h;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<f32x4*>(po + 32 * db + 8 * g) =
+            f32x4{acc[db][4 * g], acc[db][4 * g + 1], acc[db][4 * g + 2], acc[db][4 * g + 3]};
+    if (h == 0) {
+      float* pml = a.ws_ml + (int64_t)(it.part_row + rl) * 2;
+      pml[0] = m;
+      pml[1] = lsum;
+    }
+  } else {
+    const float inv = 1.f / lsum;
+    if (a.out_fp32) {
+      float* po = reinterpret_cast<float*>(a.out) + row_off + 4 * h;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<f32x4*>(po + 32 * db + 8 * g) =
+              f32x4{acc[db][4 * g] * inv, acc[db][4 * g + 1] * inv, acc[db][4 * g + 2] * inv,
+                    acc[db][4 * g + 3] * inv};
+    } else {
+      __bf16* po = reinterpret_cast<__bf16*>(a.out) + row_off + 4 * h;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 b;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) b[e] = (__bf16)(acc[db][4 * g + e] * inv);
+          *reinterpret_cast<bf16x4*>(po + 32 * db + 8 * g) = b;
+        }
+    }
+  }
+}
+
+// One launch serves every kind of work item: the block looks at its item and runs the
+// matching body, so that a ragged batch (chunk sizes 1..32 side by side) is one grid in
+// costliest-first order instead of one small grid per kind.  All bodies fit two waves per SIMD.
+//
 template <int D, int LGP>
 __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
-  constexpr int kFloats = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
-                              ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
+  constexpr int kFloats0 = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
+                               ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
+  constexpr int kFloats = kFloats0 > wide_smem_floats<D>() ? kFloats0 : wide_smem_floats<D>();
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
   const optimus_work_item_t it = a.items[blockIdx.x];
-  if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
-  else if (it.row_count <= 64) lds_tile_body<D, LGP, 1>(a, it, smem);
-  else lds_tile_body<D, LGP, 2>(a, it, smem);
+  // all row tiles of a (request, kv head) pair with more than kWideMinRows rows take the wide
+  // body, also a narrow last one, so that the siblings run the same schedule side by side
+  const int pair_rows = (a.cu_q[it.req + 1] - a.cu_q[it.req]) * a.group;
+  if (pair_rows > kWideMinRows) wide_tile_body<D, LGP>(a, it, smem);
+  else if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
+  else lds_tile_body<D, LGP, 1>(a, it, smem);
 }
 
 // Merge of split-KV partials: for each row, M = max_s m_s,

@@ -17,6 +17,7 @@ constexpr int kWavesPerBlock = 4;
 // keys), 17..128 rows the lds-tile body with 1..2 subtiles per wave (the waves split the
 // rows).  A (request, kv head) pair with more rows is cut into row tiles of 128.
 constexpr int kMaxRowsPerItem = 128;
+constexpr int kWideMinRows = 64;     // (request, kv head) pairs with more query rows take the wide body
 constexpr int kNumXcd = 8;  // accelerator dies of an MI355X; workgroup i runs on die i % 8
 // Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
 // scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
@@ -94,6 +95,7 @@ struct KernelArgs {
   int32_t num_q_heads, group, max_pages_per_req, out_fp32;
   int32_t mask_mode, block_size;
   float scale_log2;  // softmax scale * log2(e)
+  const int32_t* cu_q;  // [batch + 1] chunk offsets (the body of an item depends on its pair's rows)
 };
 
 // Kernel launchers (kernels.hip).  `stream` is a hipStream_t.

@@ -115,6 +115,20 @@ def test_wide_row_tiles(oracle_mod, Hq, Hkv, D, P):
                 tuning=dict(target_items=1 << 20, min_split_tokens=64, max_split_tokens=64))
 
 
+@pytest.mark.parametrize("P", [16, 64])
+def test_wide_rows_long_unsplit_key_range(oracle_mod, P):
+    """One work item per (request, kv head) walks more than 64 pages: the wide kernel's page
+    register is refilled on the way; chunk 40 x G 4 = 160 rows (a full and a partial row tile)."""
+    _say(f"wide rows, long unsplit range, P={P}")
+    L = [16 * 150 + 5, 64 * 70 + 33] if P == 16 else [64 * 70 + 33, 64 * 130 + 1]
+    w = inputs.make_workload("wide_long", seed=77 + P, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=P, block_size=64, prefix_len=L, chunk=[40, 24],
+                             block_inner=[0, 0], device=DEV)
+    _, plan = full_parity(oracle_mod, w, "wide long",
+                          tuning=dict(target_items=1, min_split_tokens=1 << 20, max_split_tokens=1 << 20))
+    assert plan.num_merge_items() == 0
+
+
 def test_forced_splits_and_merge(oracle_mod):
     """Tiny split size: many partials per row, including splits some waves get no tile of."""
     _say("forced splits")
