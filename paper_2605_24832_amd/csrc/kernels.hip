@@ -726,15 +726,23 @@ constexpr int wide_smem_floats() { return kWideStages * 2 * (D * 4) * 4; }
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in bits 3:0 and
 // 15:14, the other counters left at "no wait").
+#ifdef OPT_EXPERIMENT_NO_VMWAIT   // timing experiment only: results are wrong
+#define OPT_WAIT_VMCNT(n) ((void)0)
+#else
 #define OPT_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+#endif
 // Workgroup barrier without a memory fence (a fence would wait for every load in flight);
 // the empty asm statements keep the compiler from moving LDS accesses across it.
+#ifdef OPT_EXPERIMENT_NO_BARRIER  // timing experiment only: results are wrong
+#define OPT_BARRIER_NO_FENCE() asm volatile("" ::: "memory")
+#else
 #define OPT_BARRIER_NO_FENCE()          \
   do {                                  \
     asm volatile("" ::: "memory");      \
     __builtin_amdgcn_s_barrier();       \
     asm volatile("" ::: "memory");      \
   } while (0)
+#endif
 
 // 16 bytes per lane from global memory straight into LDS: lane i writes lds_addr + 16*i.
 // Written as inline asm on purpose: when the compiler sees this instruction it makes every
@@ -747,6 +755,16 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_ad
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+// Same with a wave-uniform base address in scalar registers plus a 32-bit lane offset: no
+// vector address arithmetic per load.
+__device__ __forceinline__ void load_to_lds_16(const void* base_uniform, uint32_t lane_offset,
+                                               uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_offset), "s"(base_uniform), "s"(lds_addr)
                : "memory", "m0");
 }
 
@@ -785,7 +803,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   const int lim = min(it.kv_end, vis_end);
   const bool wave_has_rows = wave * 32 < it.row_count;  // uniform per wave
 
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY, m_use = 0.f, lsum = 0.f;
   f32x16 acc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -835,6 +853,9 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   REFILL((tile_lo * kTileTokens) >> LGP);
   // item tile t -> ring stage t % S (K pieces first, then V), straight from global memory
   auto ISSUE = [&](int t) {
+#ifdef OPT_EXPERIMENT_NO_DMA          // timing experiment only: results are wrong
+    if (a.scale_log2 != -1.f) return;
+#endif
     const int tile = tile_lo + t;
     const int pi0 = (tile * kTileTokens) >> LGP;
     const int pi1 = LGP == 4 ? min(pi0 + 1, last_page) : pi0;   // clamped: its keys are masked
@@ -848,12 +869,19 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     const char* k1 = kbase + (int64_t)p1 * kspb;
     const char* v0 = vbase + (int64_t)p0 * vspb + slot0 * 2u;
     const char* v1 = vbase + (int64_t)p1 * vspb;
+    if constexpr (LGP == 4) {   // two pages per tile: the page differs between lanes
 #pragma unroll
-    for (int i = 0; i < LPT; ++i)
-      load_to_lds_16((second_page[i][0] ? k1 : k0) + ksrc[i], dst + 16u * (256 * i));
+      for (int i = 0; i < LPT; ++i)
+        load_to_lds_16((second_page[i][0] ? k1 : k0) + ksrc[i], dst + 16u * (256 * i));
 #pragma unroll
-    for (int i = 0; i < LPT; ++i)
-      load_to_lds_16((second_page[i][1] ? v1 : v0) + vsrc[i], dst + 16u * (PIECES + 256 * i));
+      for (int i = 0; i < LPT; ++i)
+        load_to_lds_16((second_page[i][1] ? v1 : v0) + vsrc[i], dst + 16u * (PIECES + 256 * i));
+    } else {
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) load_to_lds_16(k0, ksrc[i], dst + 16u * (256 * i));
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) load_to_lds_16(v0, vsrc[i], dst + 16u * (PIECES + 256 * i));
+    }
   };
   // S^T of item tile t: register v of a lane is key 32*tile + 16*(v/8) + 8h + v%8, row r32
   auto QK = [&](int t, f32x16& s) {
@@ -862,11 +890,17 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
     for (int st = 0; st < KS; ++st)
+#ifdef OPT_EXPERIMENT_NO_LDS_READ   // timing experiment only: results are wrong
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[(st + 1) % KS], qreg[st], s, 0, 0, 0);
+#else
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb[64 * st]), qreg[st], s, 0, 0, 0);
+#endif
   };
-  // running maximum after the scores of tile t: returns the reference value the tile's
-  // exponentials use and the factor the accumulators have to be scaled by before its PV
-  auto STATS = [&](int t, f32x16& s, bool masked, float& m_use, float& alpha) {
+  // row maximum of the scores of tile t (scaled); returns the candidate for the running
+  // maximum.  The reference value m_use of the exponentials follows the maximum lazily (see
+  // compute_tile): MOVE below changes it only for rows whose maximum grew by more than
+  // kMaxSlack, and only then is anything rescaled.
+  auto STATS = [&](int t, f32x16& s, bool masked) -> float {
     if (masked) {
       const int key0 = (tile_lo + t) * kTileTokens + 8 * h;
 #pragma unroll
@@ -880,16 +914,16 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
       swap32(mx, x, y);
       mx = fmaxf(x, y);
     }
-    const float m_cand = fmaxf(m, mx * sc);
-    const float m_new = (m_cand - m > kMaxSlack) ? m_cand : m;   // lazy: see compute_tile
-    m_use = m_new == -INFINITY ? 0.f : m_new;
-    alpha = fast_exp2(m - m_use);
-    m = m_new;
+    return fmaxf(m, mx * sc);
   };
   auto SOFTMAX_PV = [&](int t, const f32x16& s, float m_use, bool masked) {
     bf16x8 pt[2];
 #pragma unroll
+#ifdef OPT_EXPERIMENT_NO_EXP        // timing experiment only: results are wrong
+    for (int v = 0; v < 16; ++v) pt[v / 8][v % 8] = (__bf16)fmaf(s[v], sc, -m_use);
+#else
     for (int v = 0; v < 16; ++v) pt[v / 8][v % 8] = (__bf16)fast_exp2(fmaf(s[v], sc, -m_use));
+#endif
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int v = 0; v < 16; v += 2) {
@@ -903,7 +937,11 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 #pragma unroll
       for (int aa = 0; aa < 2; ++aa) {
         const int d = 32 * db + r32, o = 2 * aa + h;
+#ifdef OPT_EXPERIMENT_NO_LDS_READ   // timing experiment only: results are wrong
+        u32x4 vv = __builtin_bit_cast(u32x4, qreg[(2 * db + aa) % KS]);
+#else
         u32x4 vv = vb[4 * d + (o ^ ((d >> 2) & 3))];
+#endif
         if (masked) {   // keys at or beyond kv_end may hold anything: zero them
           const int cnt = it.kv_end - (key0 + 16 * aa);
           vv.x &= keep_mask(cnt); vv.y &= keep_mask(cnt - 2);
@@ -913,8 +951,16 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
       }
     }
   };
-  auto RESCALE = [&](float alpha) {
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // wave-uniform: some row moved its m
+  // take over the candidate maximum where it moved far enough; all accumulated state is then
+  // brought to the new reference (wave-uniform branch, taken on few tiles)
+  auto MOVE = [&](float m_cand) {
+    const bool moved = m_cand - m > kMaxSlack;   // m = -inf: first finite maximum moves it
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+      const float m_new = moved ? m_cand : m;
+      const float mu_new = m_new == -INFINITY ? 0.f : m_new;   // row with no visible key so far
+      const float alpha = fast_exp2(m - mu_new);
+      m = m_new;
+      m_use = mu_new;
 #pragma unroll
       for (int db = 0; db < DB; ++db) acc[db] *= alpha;
       lsum *= alpha;
@@ -932,31 +978,32 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   else OPT_WAIT_VMCNT(0);
   OPT_BARRIER_NO_FENCE();
   f32x16 sa, sb;
-  float mu_a = 0.f, mu_b = 0.f, alpha = 1.f;
+  float m_cand = -INFINITY;
   if (wave_has_rows) {
     QK(0, sa);
-    STATS(0, sa, tile_masked(0), mu_a, alpha);   // accumulators are still zero: no rescale
+    m_cand = STATS(0, sa, tile_masked(0));
+    MOVE(m_cand);
   }
 
   // One pipelined step: loads of tile t+3, scores of tile t+1, softmax and PV of tile t.
   // At its end tile t+1 (V) and tile t+2 (K) must have landed: all but the 2*LPT loads of
   // tile t+3 and the LPT V loads of tile t+2 (K is issued before V).
-  auto STEP = [&](int t, f32x16& cur, float mu_cur, f32x16& nxt, float& mu_nxt) {
+  auto STEP = [&](int t, f32x16& cur, f32x16& nxt) {
     ISSUE(t + 3);
     if (wave_has_rows) {
       QK(t + 1, nxt);
-      SOFTMAX_PV(t, cur, mu_cur, false);
-      STATS(t + 1, nxt, false, mu_nxt, alpha);
+      SOFTMAX_PV(t, cur, m_use, false);
+      m_cand = STATS(t + 1, nxt, false);
     }
     OPT_WAIT_VMCNT(3 * LPT);
     OPT_BARRIER_NO_FENCE();
-    if (wave_has_rows) RESCALE(alpha);
+    if (wave_has_rows) MOVE(m_cand);
   };
   int t = 0;
   const int n_plain = min(n, (mask_from - tile_lo * kTileTokens) / kTileTokens);  // leading unmasked tiles
   for (; t + 4 < n && t + 2 < n_plain; t += 2) {
-    STEP(t, sa, mu_a, sb, mu_b);
-    STEP(t + 1, sb, mu_b, sa, mu_a);
+    STEP(t, sa, sb);
+    STEP(t + 1, sb, sa);
   }
   // ---- remaining tiles: same step with every condition checked.  Once nothing is issued any
   // more, what may still be in flight shrinks: with tile t+2 the last one only its V loads,
@@ -966,17 +1013,16 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     if (issue) ISSUE(t + 3);
     if (wave_has_rows) {
       if (has_next) QK(t + 1, sb);
-      SOFTMAX_PV(t, sa, mu_a, tile_masked(t));
-      if (has_next) STATS(t + 1, sb, tile_masked(t + 1), mu_b, alpha);
+      SOFTMAX_PV(t, sa, m_use, tile_masked(t));
+      if (has_next) m_cand = STATS(t + 1, sb, tile_masked(t + 1));
     }
     if (issue) OPT_WAIT_VMCNT(3 * LPT);
     else if (t + 3 == n) OPT_WAIT_VMCNT(LPT);
     else OPT_WAIT_VMCNT(0);
     OPT_BARRIER_NO_FENCE();
     if (wave_has_rows && has_next) {
-      RESCALE(alpha);
+      MOVE(m_cand);
       sa = sb;
-      mu_a = mu_b;
     }
   }
 
@@ -1029,12 +1075,19 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 // matching body, so that a ragged batch (chunk sizes 1..32 side by side) is one grid in
 // costliest-first order instead of one small grid per kind.  All bodies fit two waves per SIMD.
 //
+#ifndef OPT_EXPERIMENT_OCC
+#define OPT_EXPERIMENT_OCC 2
+#endif
 template <int D, int LGP>
-__global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
+__global__ __launch_bounds__(W * 64, OPT_EXPERIMENT_OCC) void attn_kernel(KernelArgs a) {
   constexpr int kFloats0 = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
                                ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
   constexpr int kFloats = kFloats0 > wide_smem_floats<D>() ? kFloats0 : wide_smem_floats<D>();
+#if OPT_EXPERIMENT_OCC == 1   // timing experiment: one workgroup per CU (LDS above half of 160 KB)
+  __shared__ __attribute__((aligned(16))) float smem[kFloats + 8192];
+#else
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
+#endif
   const optimus_work_item_t it = a.items[blockIdx.x];
   // all row tiles of a (request, kv head) pair with more than kWideMinRows rows take the wide
   // body, also a narrow last one, so that the siblings run the same schedule side by side
@@ -1055,24 +1108,46 @@ __global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
   const int rl = blockIdx.y * 16 + (tid >> 4);
   const int ocol = (tid & 15) * CH;
   if (rl >= mi.row_count) return;
+  // Splits are taken kMergeBatch at a time with every load of a batch issued before the first
+  // use (indices past the last split are clamped to it and get weight zero), so a row costs
+  // a few memory round trips instead of one per split.
+  constexpr int kMergeBatch = 8;
+  const int ns = mi.n_splits;
+  const int64_t pr0 = mi.first_part_row + rl;
   float M = -INFINITY;
-  for (int s = 0; s < mi.n_splits; ++s)
-    M = fmaxf(M, a.ws_ml[(int64_t)(mi.first_part_row + s * mi.row_count + rl) * 2]);
+  for (int s0 = 0; s0 < ns; s0 += kMergeBatch) {
+    float mv[kMergeBatch];
+#pragma unroll
+    for (int k = 0; k < kMergeBatch; ++k)
+      mv[k] = a.ws_ml[(pr0 + (int64_t)min(s0 + k, ns - 1) * mi.row_count) * 2];
+#pragma unroll
+    for (int k = 0; k < kMergeBatch; ++k) M = fmaxf(M, mv[k]);
+  }
   const float Mu = M == -INFINITY ? 0.f : M;
   float lt = 0.f;
   float o[CH];
 #pragma unroll
   for (int c = 0; c < CH; ++c) o[c] = 0.f;
-  for (int s = 0; s < mi.n_splits; ++s) {
-    const int64_t pr = mi.first_part_row + s * mi.row_count + rl;
-    const float w = fast_exp2(a.ws_ml[pr * 2] - Mu);
-    lt = fmaf(w, a.ws_ml[pr * 2 + 1], lt);
-    const float* po = a.ws_o + pr * D + ocol;
+  for (int s0 = 0; s0 < ns; s0 += kMergeBatch) {
+    float mv[kMergeBatch], lv[kMergeBatch];
+    f32x4 ov[kMergeBatch][CH / 4];
 #pragma unroll
-    for (int c = 0; c < CH; c += 4) {
-      f32x4 v = *reinterpret_cast<const f32x4*>(po + c);
-      o[c] = fmaf(w, v[0], o[c]); o[c + 1] = fmaf(w, v[1], o[c + 1]);
-      o[c + 2] = fmaf(w, v[2], o[c + 2]); o[c + 3] = fmaf(w, v[3], o[c + 3]);
+    for (int k = 0; k < kMergeBatch; ++k) {
+      const int64_t pr = pr0 + (int64_t)min(s0 + k, ns - 1) * mi.row_count;
+      mv[k] = a.ws_ml[pr * 2];
+      lv[k] = a.ws_ml[pr * 2 + 1];
+#pragma unroll
+      for (int c = 0; c < CH / 4; ++c) ov[k][c] = *reinterpret_cast<const f32x4*>(a.ws_o + pr * D + ocol + 4 * c);
+    }
+#pragma unroll
+    for (int k = 0; k < kMergeBatch; ++k) {
+      const float w = s0 + k < ns ? fast_exp2(mv[k] - Mu) : 0.f;
+      lt = fmaf(w, lv[k], lt);
+#pragma unroll
+      for (int c = 0; c < CH / 4; ++c) {
+        o[4 * c] = fmaf(w, ov[k][c][0], o[4 * c]); o[4 * c + 1] = fmaf(w, ov[k][c][1], o[4 * c + 1]);
+        o[4 * c + 2] = fmaf(w, ov[k][c][2], o[4 * c + 2]); o[4 * c + 3] = fmaf(w, ov[k][c][3], o[4 * c + 3]);
+      }
     }
   }
   const float inv = 1.f / lt;
