@@ -76,7 +76,8 @@ typedef struct {
   int32_t num_pages;         /* pool size, for block-table validation           */
   int32_t max_pages_per_req; /* row stride of the block table                   */
   int32_t reserved0;
-  int64_t k_stride_page, k_stride_head; /* elements; multiples of 8             */
+  int64_t k_stride_page, k_stride_head; /* elements; multiples of 8; page strides
+                                           below 2^31                            */
   int64_t v_stride_page, v_stride_head; /* elements; multiples of 8             */
 } optimus_attn_params_t;
 

@@ -583,9 +583,6 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
     }
   };
   auto COMPUTE = [&](int buf, int t) {
-#ifdef OPT_EXPERIMENT_SKIP_COMPUTE
-    if (a.scale_log2 != -1.f) return;   // timing experiment only: results are wrong
-#endif
     if (!wave_has_rows) return;
     const int key_base = (tile_lo + t) * kTileTokens;
     const bool masked = key_base + kTileTokens > mask_from;
@@ -726,23 +723,15 @@ constexpr int wide_smem_floats() { return kWideStages * 2 * (D * 4) * 4; }
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in bits 3:0 and
 // 15:14, the other counters left at "no wait").
-#ifdef OPT_EXPERIMENT_NO_VMWAIT   // timing experiment only: results are wrong
-#define OPT_WAIT_VMCNT(n) ((void)0)
-#else
 #define OPT_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-#endif
 // Workgroup barrier without a memory fence (a fence would wait for every load in flight);
 // the empty asm statements keep the compiler from moving LDS accesses across it.
-#ifdef OPT_EXPERIMENT_NO_BARRIER  // timing experiment only: results are wrong
-#define OPT_BARRIER_NO_FENCE() asm volatile("" ::: "memory")
-#else
 #define OPT_BARRIER_NO_FENCE()          \
   do {                                  \
     asm volatile("" ::: "memory");      \
     __builtin_amdgcn_s_barrier();       \
     asm volatile("" ::: "memory");      \
   } while (0)
-#endif
 
 // 16 bytes per lane from global memory straight into LDS: lane i writes lds_addr + 16*i.
 // Written as inline asm on purpose: when the compiler sees this instruction it makes every
@@ -814,7 +803,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   const int last_page = (it.kv_end - 1) >> LGP;
   const char* kbase = reinterpret_cast<const char*>(a.k_pool + (int64_t)it.kv_head * a.k_stride_head);
   const char* vbase = reinterpret_cast<const char*>(a.v_pool + (int64_t)it.kv_head * a.v_stride_head);
-  const int64_t kspb = a.k_stride_page * 2, vspb = a.v_stride_page * 2;
+  const uint32_t kspb32 = (uint32_t)(a.k_stride_page * 2), vspb32 = (uint32_t)(a.v_stride_page * 2);
   const float sc = a.scale_log2;
   const int tile_lo = it.kv_begin / kTileTokens;
   const int n = (it.kv_end + kTileTokens - 1) / kTileTokens - tile_lo;
@@ -853,9 +842,6 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   REFILL((tile_lo * kTileTokens) >> LGP);
   // item tile t -> ring stage t % S (K pieces first, then V), straight from global memory
   auto ISSUE = [&](int t) {
-#ifdef OPT_EXPERIMENT_NO_DMA          // timing experiment only: results are wrong
-    if (a.scale_log2 != -1.f) return;
-#endif
     const int tile = tile_lo + t;
     const int pi0 = (tile * kTileTokens) >> LGP;
     const int pi1 = LGP == 4 ? min(pi0 + 1, last_page) : pi0;   // clamped: its keys are masked
@@ -865,10 +851,12 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     // low 32 bits of a generic pointer into LDS = the LDS byte address
     const uint32_t dst = (uint32_t)(uintptr_t)(sm + (t & (S - 1)) * STAGE + wave * 64);
     const uint32_t slot0 = LGP == 4 ? 0u : (uint32_t)((tile * kTileTokens) & (P - 1));
-    const char* k0 = kbase + (int64_t)p0 * kspb + slot0 * 16u;
-    const char* k1 = kbase + (int64_t)p1 * kspb;
-    const char* v0 = vbase + (int64_t)p0 * vspb + slot0 * 2u;
-    const char* v1 = vbase + (int64_t)p1 * vspb;
+    // page ids are non-negative and the page stride fits 32 bits (checked by the launcher):
+    // one 32 x 32 -> 64 bit multiply per base
+    const char* k0 = kbase + (uint64_t)(uint32_t)p0 * kspb32 + slot0 * 16u;
+    const char* k1 = kbase + (uint64_t)(uint32_t)p1 * kspb32;
+    const char* v0 = vbase + (uint64_t)(uint32_t)p0 * vspb32 + slot0 * 2u;
+    const char* v1 = vbase + (uint64_t)(uint32_t)p1 * vspb32;
     if constexpr (LGP == 4) {   // two pages per tile: the page differs between lanes
 #pragma unroll
       for (int i = 0; i < LPT; ++i)
@@ -890,11 +878,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
     for (int st = 0; st < KS; ++st)
-#ifdef OPT_EXPERIMENT_NO_LDS_READ   // timing experiment only: results are wrong
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[(st + 1) % KS], qreg[st], s, 0, 0, 0);
-#else
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb[64 * st]), qreg[st], s, 0, 0, 0);
-#endif
   };
   // row maximum of the scores of tile t (scaled); returns the candidate for the running
   // maximum.  The reference value m_use of the exponentials follows the maximum lazily (see
@@ -919,11 +903,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   auto SOFTMAX_PV = [&](int t, const f32x16& s, float m_use, bool masked) {
     bf16x8 pt[2];
 #pragma unroll
-#ifdef OPT_EXPERIMENT_NO_EXP        // timing experiment only: results are wrong
-    for (int v = 0; v < 16; ++v) pt[v / 8][v % 8] = (__bf16)fmaf(s[v], sc, -m_use);
-#else
     for (int v = 0; v < 16; ++v) pt[v / 8][v % 8] = (__bf16)fast_exp2(fmaf(s[v], sc, -m_use));
-#endif
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int v = 0; v < 16; v += 2) {
@@ -937,11 +917,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 #pragma unroll
       for (int aa = 0; aa < 2; ++aa) {
         const int d = 32 * db + r32, o = 2 * aa + h;
-#ifdef OPT_EXPERIMENT_NO_LDS_READ   // timing experiment only: results are wrong
-        u32x4 vv = __builtin_bit_cast(u32x4, qreg[(2 * db + aa) % KS]);
-#else
         u32x4 vv = vb[4 * d + (o ^ ((d >> 2) & 3))];
-#endif
         if (masked) {   // keys at or beyond kv_end may hold anything: zero them
           const int cnt = it.kv_end - (key0 + 16 * aa);
           vv.x &= keep_mask(cnt); vv.y &= keep_mask(cnt - 2);
@@ -1075,19 +1051,12 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 // matching body, so that a ragged batch (chunk sizes 1..32 side by side) is one grid in
 // costliest-first order instead of one small grid per kind.  All bodies fit two waves per SIMD.
 //
-#ifndef OPT_EXPERIMENT_OCC
-#define OPT_EXPERIMENT_OCC 2
-#endif
 template <int D, int LGP>
-__global__ __launch_bounds__(W * 64, OPT_EXPERIMENT_OCC) void attn_kernel(KernelArgs a) {
+__global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
   constexpr int kFloats0 = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
                                ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
   constexpr int kFloats = kFloats0 > wide_smem_floats<D>() ? kFloats0 : wide_smem_floats<D>();
-#if OPT_EXPERIMENT_OCC == 1   // timing experiment: one workgroup per CU (LDS above half of 160 KB)
-  __shared__ __attribute__((aligned(16))) float smem[kFloats + 8192];
-#else
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
-#endif
   const optimus_work_item_t it = a.items[blockIdx.x];
   // all row tiles of a (request, kv head) pair with more than kWideMinRows rows take the wide
   // body, also a narrow last one, so that the siblings run the same schedule side by side

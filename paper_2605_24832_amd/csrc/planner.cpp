@@ -24,6 +24,9 @@ int validate_params(const optimus_attn_params_t& p) {
   const int64_t strides[4] = {p.k_stride_page, p.k_stride_head, p.v_stride_page, p.v_stride_head};
   for (int64_t s : strides)
     if (s < 0 || s % 8 != 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  // a page stride is used as a 32-bit byte count by the kernels
+  if (p.k_stride_page >= ((int64_t)1 << 31) || p.v_stride_page >= ((int64_t)1 << 31))
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
   // tiles of different heads / pages must not overlap
   if (p.num_kv_heads > 1 && (p.k_stride_head < tile || p.v_stride_head < tile))
     return OPTIMUS_ERR_INVALID_ARGUMENT;

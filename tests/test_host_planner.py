@@ -42,6 +42,7 @@ def test_status_strings():
     (dict(num_q_heads=30), -2), (dict(head_dim=96), -2), (dict(page_size=8), -2),
     (dict(kv_layout=0), -2), (dict(mask_mode=2), -1), (dict(out_dtype=3), -1),
     (dict(block_size=0), -1), (dict(k_stride_head=100), -1), (dict(k_stride_page=1024), -1),
+    (dict(v_stride_page=1 << 31), -1),
 ])
 def test_plan_create_rejects_bad_params(bad, code):
     with pytest.raises(OptimusError) as e:
