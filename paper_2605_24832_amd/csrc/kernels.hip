@@ -19,8 +19,11 @@
 //   slot-contiguous, makes every wave-wide load a contiguous run), each wave
 //   keeps its own online-softmax state and the waves are merged through LDS.
 //
-//   17..128 rows ("lds-tile" body): all waves walk the same tiles, staged once
-//   per workgroup in LDS, and each wave owns 16 or 32 of the rows.
+//   17..64 rows ("lds-tile" body): all waves walk the same tiles, staged once
+//   per workgroup in LDS, and each wave owns 16 of the rows.
+//
+//   pairs with more than 64 rows ("wide" body, further down): 32 rows per wave,
+//   32x32x16 MFMA, tiles loaded from global memory straight into LDS.
 //
 // Key ranges split over several work items leave partials that the merge
 // kernel combines (a fused "last block merges" variant was measured 4x slower:
@@ -446,8 +449,8 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
   }
 }
 
-// attention kernel for wide row tiles ("lds-tile"): up to 64*NT query rows per
-// work item.  All 4 waves walk the same 32-key tiles, staged once per workgroup
+// attention body for medium row tiles ("lds-tile"): up to 64*NT query rows per
+// work item (instantiated with NT = 1; wider pairs take the wide body).  All 4 waves walk the same 32-key tiles, staged once per workgroup
 // in LDS (coalesced global loads -> registers -> ds_write, double-buffered, two
 // tiles of loads in flight), and each wave owns NT x 16 of the rows, so K/V
 // leave HBM once however many query heads and chunk tokens share them.
