@@ -15,5 +15,10 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def oracle_mod():
     import oracle
+    # tests/test_oracle_mutations.py re-runs the pin files against oracle builds with a planted
+    # mistake: it points this variable at the mutant's shared library (CPU only)
+    mutant = os.environ.get("ORACLE_MUTANT_LIB")
+    if mutant:
+        oracle._LIB = mutant
     oracle.build()
     return oracle

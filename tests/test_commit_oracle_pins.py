@@ -67,6 +67,14 @@ def test_progress_rule_commits_the_most_confident_token(oracle_mod):
         assert com[lo:hi].sum() == 1 and com[lo + int(np.argmax(conf[lo:hi]))] == 1
     _, _, com0 = oracle_mod.commit(bits(x), V, 0.9, cu, 0)
     assert com0.sum() == 1 and com0[4] == 1
+    # the last position of a request counts like any other: as the only sure one it keeps the
+    # rule from firing, as the most confident of a flat request it is the one forced
+    z = torch.randn(6, V, generator=g)
+    z[2, 5] += 30.0                             # request 0 = rows 0..2: its last row is sure
+    z[5, 9] += 2.0                              # request 1 = rows 3..5: its last row is the best, below 0.9
+    _, confz, comz = oracle_mod.commit(bits(z), V, 0.9, [0, 3, 6], 1)
+    assert confz[5] < 0.9 and int(np.argmax(confz[3:6])) == 2
+    np.testing.assert_array_equal(comz, [0, 0, 1, 0, 0, 1])
     # ties inside a request: the first one is forced
     y = torch.zeros(4, V)
     _, _, com3 = oracle_mod.commit(bits(y), V, 0.9, [0, 4], 1)
