@@ -55,7 +55,7 @@ struct optimus_attn_plan {
   size_t dev_cap = 0;          // in int32
   std::vector<int32_t*> retired;  // outgrown device buffers, freed with the plan
   // offsets (int32 units) into dev_buf
-  size_t off_items = 0, off_merges = 0, off_token_req = 0, off_cu_q = 0, off_prefix = 0, off_bstart = 0;
+  size_t off_items = 0, off_merges = 0, off_runs = 0, off_cu_q = 0, off_prefix = 0, off_bstart = 0;
 
   bool timing = false;
   std::vector<hipEvent_t> events;  // pairs (start, stop), created on demand
@@ -129,7 +129,7 @@ int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int
   auto take = [&](size_t n_i32) { size_t o = off; off += (n_i32 + 3) & ~size_t(3); return o; };
   plan->off_items = take(hp.items.size() * 8);
   plan->off_merges = take(hp.merges.size() * 8);
-  plan->off_token_req = take(hp.token_req.size());
+  plan->off_runs = take(hp.append_runs.size());
   plan->off_cu_q = take(hp.cu_q.size());
   plan->off_prefix = take(hp.prefix_len.size());
   plan->off_bstart = take(hp.block_start.size());
@@ -164,8 +164,8 @@ int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int
   int32_t* h = plan->staging[sl];
   if (!hp.items.empty()) std::memcpy(h + plan->off_items, hp.items.data(), hp.items.size() * 32);
   if (!hp.merges.empty()) std::memcpy(h + plan->off_merges, hp.merges.data(), hp.merges.size() * 32);
-  if (!hp.token_req.empty())
-    std::memcpy(h + plan->off_token_req, hp.token_req.data(), hp.token_req.size() * 4);
+  if (!hp.append_runs.empty())
+    std::memcpy(h + plan->off_runs, hp.append_runs.data(), hp.append_runs.size() * 4);
   std::memcpy(h + plan->off_cu_q, hp.cu_q.data(), hp.cu_q.size() * 4);
   std::memcpy(h + plan->off_prefix, hp.prefix_len.data(), hp.prefix_len.size() * 4);
   std::memcpy(h + plan->off_bstart, hp.block_start.data(), hp.block_start.size() * 4);
@@ -204,8 +204,8 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
   if (rc != OPTIMUS_OK) return rc;
   const int32_t* d = plan->dev_buf;
   return launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
-                          (const uint16_t*)v_new, block_table, d + plan->off_token_req,
-                          d + plan->off_cu_q, d + plan->off_prefix, plan->host.total_q, hip_stream);
+                          (const uint16_t*)v_new, block_table, d + plan->off_runs,
+                          (int32_t)(plan->host.append_runs.size() / 4), hip_stream);
 }
 
 int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,

@@ -1144,30 +1144,69 @@ __global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
   }
 }
 
-// KV append: chunk token j of request i -> logical slot L_i + j of the pool.
-// Block = (token, kv head); threads 0..D/8-1 copy K in 16-byte groups, all D
-// threads copy one V element each (slot-contiguous layout: stride P).
+// KV append: chunk token j of request i -> logical slot L_i + j of the pool.  The planner cuts
+// every chunk into runs of up to 8 tokens whose slots lie in one aligned group of 8 slots (so
+// in one page).  Block = run; the threads walk all kv heads.  K: 16-byte groups per token.
+// V is slot-contiguous (stride P between d), so a run is written per (head, d) with the
+// widest aligned stores that fit (16, 8, 4 or 2 bytes): a 2-byte store costs a whole 32-byte
+// memory write, which made the token-by-token version write 9x its payload.
+struct AppendRun { int32_t req, token0, slot0, count; };
+
 template <int D>
-__global__ __launch_bounds__(D) void kv_append_kernel(
+__global__ __launch_bounds__(256) void kv_append_kernel(
     uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const uint16_t* __restrict__ k_new,
     const uint16_t* __restrict__ v_new, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ token_req, const int32_t* __restrict__ cu_q,
-    const int32_t* __restrict__ prefix_len, int num_kv_heads, int page_size, int lgp,
+    const AppendRun* __restrict__ runs, int num_kv_heads, int page_size, int lgp,
     int max_pages_per_req, int64_t k_stride_page, int64_t k_stride_head, int64_t v_stride_page,
     int64_t v_stride_head) {
-  const int t = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
-  const int i = token_req[t];
-  const int n = prefix_len[i] + (t - cu_q[i]);
-  const int64_t page = block_table[(int64_t)i * max_pages_per_req + (n >> lgp)];
-  const int slot = n & (page_size - 1);
-  const int64_t src = ((int64_t)t * num_kv_heads + g) * D;
-  if (d < D / 8) {
-    const u32x4 x = *reinterpret_cast<const u32x4*>(k_new + src + d * 8);
-    *reinterpret_cast<u32x4*>(k_pool + page * k_stride_page + (int64_t)g * k_stride_head +
-                              ((int64_t)d * page_size + slot) * 8) = x;
+  const AppendRun r = runs[blockIdx.x];
+  const int64_t page = block_table[(int64_t)r.req * max_pages_per_req + (r.slot0 >> lgp)];
+  const int slot = r.slot0 & (page_size - 1);
+  const int64_t row = (int64_t)num_kv_heads * D;       // elements per token of k_new / v_new
+  const uint16_t* ksrc = k_new + (int64_t)r.token0 * row;
+  const uint16_t* vsrc = v_new + (int64_t)r.token0 * row;
+  uint16_t* kp = k_pool + page * k_stride_page;
+  uint16_t* vp = v_pool + page * v_stride_page;
+  const int kpieces = num_kv_heads * (D / 8);
+  for (int e = threadIdx.x; e < r.count * kpieces; e += 256) {
+    const int j = e / kpieces, rem = e - j * kpieces;
+    const int g = rem / (D / 8), dg = rem % (D / 8);
+    const u32x4 x = *reinterpret_cast<const u32x4*>(ksrc + j * row + g * D + dg * 8);
+    *reinterpret_cast<u32x4*>(kp + (int64_t)g * k_stride_head + ((int64_t)dg * page_size + slot + j) * 8) = x;
   }
-  v_pool[page * v_stride_page + (int64_t)g * v_stride_head + (int64_t)d * page_size + slot] =
-      v_new[src + d];
+  for (int e = threadIdx.x; e < num_kv_heads * D; e += 256) {
+    const int g = e / D, d = e % D;
+    // w[p]: value for position p of the aligned group of 8 slots (register indices are
+    // compile-time; first and count are the same for the whole block: no divergence)
+    const int first = slot & 7;
+    uint16_t* dst = vp + (int64_t)g * v_stride_head + (int64_t)d * page_size + (slot - first);
+    uint32_t w[8];
+    bool on[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const int j = p - first;
+      on[p] = j >= 0 && j < r.count;
+      w[p] = on[p] ? vsrc[j * row + e] : 0u;
+    }
+    if (r.count == 8) {
+      *reinterpret_cast<u32x4*>(dst) =
+          u32x4{w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16)};
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; q += 4) {
+        if (on[q] && on[q + 1] && on[q + 2] && on[q + 3]) {
+          *reinterpret_cast<u32x2*>(dst + q) = u32x2{w[q] | (w[q + 1] << 16), w[q + 2] | (w[q + 3] << 16)};
+        } else {
+#pragma unroll
+          for (int p = q; p < q + 4; p += 2) {
+            if (on[p] && on[p + 1]) *reinterpret_cast<uint32_t*>(dst + p) = w[p] | (w[p + 1] << 16);
+            else if (on[p]) dst[p] = (uint16_t)w[p];
+            else if (on[p + 1]) dst[p + 1] = (uint16_t)w[p + 1];
+          }
+        }
+      }
+    }
+  }
 }
 
 // ------------------------------------------------------------------ launchers
@@ -1213,21 +1252,21 @@ int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_
 
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
-                     const int32_t* token_req, const int32_t* cu_q, const int32_t* prefix_len,
-                     int32_t total_q, void* stream) {
-  if (total_q <= 0) return OPTIMUS_OK;
+                     const int32_t* runs, int32_t n_runs, void* stream) {
+  if (n_runs <= 0) return OPTIMUS_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int lgp = 0;
   while ((1 << lgp) < p.page_size) ++lgp;
-  const dim3 grid(total_q, p.num_kv_heads);
+  const dim3 grid(n_runs), block(256);
+  const AppendRun* r = reinterpret_cast<const AppendRun*>(runs);
   if (p.head_dim == 128)
-    hipLaunchKernelGGL((kv_append_kernel<128>), grid, dim3(128), 0, s, k_pool, v_pool, k_new, v_new,
-                       block_table, token_req, cu_q, prefix_len, p.num_kv_heads, p.page_size, lgp,
+    hipLaunchKernelGGL((kv_append_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
+                       block_table, r, p.num_kv_heads, p.page_size, lgp,
                        p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
                        p.v_stride_head);
   else
-    hipLaunchKernelGGL((kv_append_kernel<64>), grid, dim3(64), 0, s, k_pool, v_pool, k_new, v_new,
-                       block_table, token_req, cu_q, prefix_len, p.num_kv_heads, p.page_size, lgp,
+    hipLaunchKernelGGL((kv_append_kernel<64>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
+                       block_table, r, p.num_kv_heads, p.page_size, lgp,
                        p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
                        p.v_stride_head);
   hipError_t e = hipGetLastError();

@@ -52,7 +52,9 @@ struct HostPlan {
   int32_t total_q = 0;
   std::vector<optimus_work_item_t> items;  // costliest first, interleaved over 8 XCD lanes
   std::vector<MergeItem> merges;
-  std::vector<int32_t> token_req;   // [T] request of each query token
+  // KV append runs, 4 x int32 each (request, first token, first logical slot, count <= 8):
+  // the slots of a run lie in one aligned group of 8
+  std::vector<int32_t> append_runs;
   std::vector<int32_t> cu_q, prefix_len, block_start;
   int64_t part_rows = 0;            // rows of split-KV partials in the workspace
   size_t workspace_bytes = 0;
@@ -65,7 +67,7 @@ struct HostPlan {
 
   void reset() {
     batch = 0; total_q = 0; part_rows = 0; workspace_bytes = 0;
-    items.clear(); merges.clear(); token_req.clear(); cu_q.clear(); prefix_len.clear();
+    items.clear(); merges.clear(); append_runs.clear(); cu_q.clear(); prefix_len.clear();
     block_start.clear();
   }
 };
@@ -105,8 +107,7 @@ int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_
                  void* stream);
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
-                     const int32_t* token_req, const int32_t* cu_q, const int32_t* prefix_len,
-                     int32_t total_q, void* stream);
+                     const int32_t* runs, int32_t n_runs, void* stream);
 
 void set_hip_error(int hip_err, const char* where);
 

@@ -73,9 +73,16 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   hp.cu_q.assign(cu_q, cu_q + batch + 1);
   hp.prefix_len.assign(prefix_len, prefix_len + batch);
   hp.block_start.assign(block_start, block_start + batch);
-  hp.token_req.resize(hp.total_q);
-  for (int i = 0; i < batch; ++i)
-    for (int t = cu_q[i]; t < cu_q[i + 1]; ++t) hp.token_req[t] = i;
+  hp.append_runs.clear();
+  for (int i = 0; i < batch; ++i) {
+    const int c = cu_q[i + 1] - cu_q[i];
+    for (int j = 0; j < c;) {
+      const int slot = prefix_len[i] + j;
+      const int count = std::min(c - j, 8 - (slot & 7));   // up to the end of the aligned group
+      hp.append_runs.insert(hp.append_runs.end(), {i, cu_q[i] + j, slot, count});
+      j += count;
+    }
+  }
 
   // ---- how many keys one work item scans ----
   double total_cost = 0.0;
