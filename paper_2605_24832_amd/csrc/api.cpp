@@ -180,9 +180,8 @@ int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int
 static int flush_upload(optimus_attn_plan* plan, hipStream_t s) {
   if (!plan->dirty) return OPTIMUS_OK;
   const int sl = plan->slot;
-  OPT_HIP(hipMemcpyAsync(plan->dev_buf, plan->staging[sl], plan->upload_i32 * sizeof(int32_t),
-                         hipMemcpyHostToDevice, s),
-          "hipMemcpyAsync(work list)");
+  const int rc = launch_upload(plan->dev_buf, plan->staging[sl], plan->upload_i32, s);
+  if (rc != OPTIMUS_OK) return rc;
   OPT_HIP(hipEventRecord(plan->staging_done[sl], s), "hipEventRecord(staging)");
   plan->staging_busy[sl] = true;
   plan->dirty = false;

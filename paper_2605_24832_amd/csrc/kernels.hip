@@ -1274,4 +1274,22 @@ int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t*
   return OPTIMUS_OK;
 }
 
+__global__ __launch_bounds__(256) void upload_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                     size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+int launch_upload(int32_t* dst_device, const int32_t* src_pinned_host, size_t n_i32, void* stream) {
+  if (n_i32 == 0) return OPTIMUS_OK;
+  if (n_i32 % 4 != 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  const size_t n = n_i32 / 4;
+  hipLaunchKernelGGL(upload_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(stream), reinterpret_cast<u32x4*>(dst_device),
+                     reinterpret_cast<const u32x4*>(src_pinned_host), n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error((int)e, "upload kernel launch"); return OPTIMUS_ERR_HIP; }
+  return OPTIMUS_OK;
+}
+
 }  // namespace optimus

@@ -109,6 +109,10 @@ int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t*
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
                      const int32_t* runs, int32_t n_runs, void* stream);
 
+// Copy n_i32 (a multiple of 4) int32 from pinned host memory to device memory with a kernel on
+// `stream` (shorter than the copy engine's start-up for the few tens of KB of a work list).
+int launch_upload(int32_t* dst_device, const int32_t* src_pinned_host, size_t n_i32, void* stream);
+
 void set_hip_error(int hip_err, const char* where);
 
 }  // namespace optimus
