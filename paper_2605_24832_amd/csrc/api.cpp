@@ -41,8 +41,10 @@ struct optimus_attn_plan {
 
   // Device copy of the descriptors and the work list.  plan_update fills one
   // slot of a ring of pinned staging buffers; the first device call after it
-  // enqueues the host-to-device copy on the caller's stream, so the upload is
-  // ordered behind the kernels of earlier iterations that still read the list.
+  // enqueues the host-to-device copy on the caller's stream (kernel threads read
+  // the pinned buffer: cheaper than the copy engine for a few tens of KB), so the
+  // upload is ordered behind the kernels of earlier iterations that still read
+  // the list.
   static constexpr int kRing = 4;
   int32_t* staging[kRing] = {nullptr, nullptr, nullptr, nullptr};
   size_t staging_cap[kRing] = {0, 0, 0, 0};   // in int32
@@ -199,12 +201,24 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
     return OPTIMUS_ERR_INVALID_ARGUMENT;
   int rc = use_device(plan);
   if (rc != OPTIMUS_OK) return rc;
-  rc = flush_upload(plan, reinterpret_cast<hipStream_t>(hip_stream));
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  const int n_runs = (int32_t)(plan->host.append_runs.size() / 4);
+  if (!plan->dirty) {
+    return launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
+                            (const uint16_t*)v_new, block_table, plan->dev_buf + plan->off_runs, n_runs,
+                            nullptr, nullptr, 0, hip_stream);
+  }
+  // a work-list upload is pending: it rides in the same launch, and the runs are read from the
+  // pinned copy
+  const int sl = plan->slot;
+  rc = launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
+                        (const uint16_t*)v_new, block_table, plan->staging[sl] + plan->off_runs, n_runs,
+                        plan->dev_buf, plan->staging[sl], plan->upload_i32, hip_stream);
   if (rc != OPTIMUS_OK) return rc;
-  const int32_t* d = plan->dev_buf;
-  return launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
-                          (const uint16_t*)v_new, block_table, d + plan->off_runs,
-                          (int32_t)(plan->host.append_runs.size() / 4), hip_stream);
+  OPT_HIP(hipEventRecord(plan->staging_done[sl], s), "hipEventRecord(staging)");
+  plan->staging_busy[sl] = true;
+  plan->dirty = false;
+  return OPTIMUS_OK;
 }
 
 int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,

@@ -1158,8 +1158,17 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
     const uint16_t* __restrict__ v_new, const int32_t* __restrict__ block_table,
     const AppendRun* __restrict__ runs, int num_kv_heads, int page_size, int lgp,
     int max_pages_per_req, int64_t k_stride_page, int64_t k_stride_head, int64_t v_stride_page,
-    int64_t v_stride_head) {
-  const AppendRun r = runs[blockIdx.x];
+    int64_t v_stride_head, u32x4* __restrict__ upload_dst, const u32x4* __restrict__ upload_src,
+    size_t upload_n, int upload_blocks) {
+  // The first upload_blocks workgroups carry a pending work-list upload (pinned host memory ->
+  // device) so that it does not cost a launch of its own; `runs` then points into the pinned
+  // copy, which is complete before the launch, not into the device copy being written.
+  if ((int)blockIdx.x < upload_blocks) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < upload_n) upload_dst[i] = upload_src[i];
+    return;
+  }
+  const AppendRun r = runs[blockIdx.x - upload_blocks];
   const int64_t page = block_table[(int64_t)r.req * max_pages_per_req + (r.slot0 >> lgp)];
   const int slot = r.slot0 & (page_size - 1);
   const int64_t row = (int64_t)num_kv_heads * D;       // elements per token of k_new / v_new
@@ -1252,23 +1261,29 @@ int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_
 
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
-                     const int32_t* runs, int32_t n_runs, void* stream) {
-  if (n_runs <= 0) return OPTIMUS_OK;
+                     const int32_t* runs, int32_t n_runs, int32_t* upload_dst,
+                     const int32_t* upload_src, size_t upload_i32, void* stream) {
+  if (n_runs <= 0) return upload_i32 ? launch_upload(upload_dst, upload_src, upload_i32, stream) : OPTIMUS_OK;
+  if (upload_i32 % 4 != 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  const size_t up_n = upload_i32 / 4;
+  const int up_blocks = (int)((up_n + 255) / 256);
+  u32x4* ud = reinterpret_cast<u32x4*>(upload_dst);
+  const u32x4* us = reinterpret_cast<const u32x4*>(upload_src);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   int lgp = 0;
   while ((1 << lgp) < p.page_size) ++lgp;
-  const dim3 grid(n_runs), block(256);
+  const dim3 grid(n_runs + up_blocks), block(256);
   const AppendRun* r = reinterpret_cast<const AppendRun*>(runs);
   if (p.head_dim == 128)
     hipLaunchKernelGGL((kv_append_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
                        block_table, r, p.num_kv_heads, p.page_size, lgp,
                        p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
-                       p.v_stride_head);
+                       p.v_stride_head, ud, us, up_n, up_blocks);
   else
     hipLaunchKernelGGL((kv_append_kernel<64>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
                        block_table, r, p.num_kv_heads, p.page_size, lgp,
                        p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
-                       p.v_stride_head);
+                       p.v_stride_head, ud, us, up_n, up_blocks);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error((int)e, "kv_append kernel launch"); return OPTIMUS_ERR_HIP; }
   return OPTIMUS_OK;

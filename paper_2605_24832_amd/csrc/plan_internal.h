@@ -105,9 +105,12 @@ int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int32_
                      void* stream);
 int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges,
                  void* stream);
+// `runs` may live in pinned host memory.  If upload_i32 > 0 the launch also copies that many
+// int32 (a multiple of 4) from upload_src (pinned host) to upload_dst (device).
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
-                     const int32_t* runs, int32_t n_runs, void* stream);
+                     const int32_t* runs, int32_t n_runs, int32_t* upload_dst,
+                     const int32_t* upload_src, size_t upload_i32, void* stream);
 
 // Copy n_i32 (a multiple of 4) int32 from pinned host memory to device memory with a kernel on
 // `stream` (shorter than the copy engine's start-up for the few tens of KB of a work list).
