@@ -318,3 +318,33 @@ def test_config4_long_context(oracle_mod, chunk):
     w = inputs.make_config(4, device=DEV, chunk=chunk)
     assert w.extra["peaked_positions"] > 0
     sampled_parity(oracle_mod, w, f"config4 chunk={chunk}", requests=[1], kv_heads=[5])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_workloads(oracle_mod, seed):
+    """Seeded random shapes, descriptors and planner tunings (every body, every page size,
+    both mask modes, splits of any size): full parity against the oracle."""
+    rng = np.random.RandomState(9000 + seed)
+    D = int(rng.choice([64, 128]))
+    P = int(rng.choice([16, 32, 64, 128]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 7, 8]))
+    B = int(rng.choice([32, 64, 128]))
+    mask_mode = int(rng.choice([0, 1]))
+    R = int(rng.randint(1, 6))
+    d_in = rng.randint(0, B, size=R)                                  # cached tokens inside the block
+    if mask_mode == 0:
+        c = np.array([rng.randint(0, B - d + 1) for d in d_in])      # chunk stays in the block
+    else:
+        c = rng.randint(0, B + 1, size=R)                             # may cross into the next block
+    if c.sum() == 0:
+        c[0] = 1                                                      # d_in < B: one token always fits
+    blocks_before = rng.randint(0, 2000 // B, size=R)
+    L = blocks_before * B + d_in
+    _say(f"random seed={seed} D={D} P={P} Hq={Hkv * G} Hkv={Hkv} B={B} mask={mask_mode} L={L.tolist()} c={c.tolist()}")
+    w = inputs.make_workload("rnd", seed=7000 + seed, num_q_heads=Hkv * G, num_kv_heads=Hkv, head_dim=D,
+                             page_size=P, block_size=B, prefix_len=L, chunk=c, block_inner=d_in,
+                             mask_mode=mask_mode, device=DEV)
+    split = int(rng.choice([0, 32, 64, 256, 1024]))
+    tuning = None if split == 0 else dict(target_items=1 << 20, min_split_tokens=split, max_split_tokens=split)
+    full_parity(oracle_mod, w, f"random {seed}", tuning=tuning)
