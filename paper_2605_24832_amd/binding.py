@@ -87,7 +87,7 @@ def load_library():
         vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
         lib.optimus_attn_plan_create.argtypes = [ctypes.POINTER(_CParams), ctypes.c_int,
                                                  ctypes.POINTER(vp)]
-        lib.optimus_attn_plan_update.argtypes = [vp, i32, i32p, i32p, i32p, i32p,
+        lib.optimus_attn_plan_update.argtypes = [vp, i32, vp, vp, vp, vp,
                                                  ctypes.POINTER(ctypes.c_size_t)]
         lib.optimus_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.optimus_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -158,28 +158,41 @@ class AttnParams:
         return c
 
 
-def _ptr(t) -> ctypes.c_void_p:
-    """Device pointer of a torch tensor (None -> NULL)."""
+# The marshalling below runs two or three times per decoding iteration, next to kernels of a
+# few microseconds: addresses are passed as plain integers (the argtypes are void pointers).
+
+def _ptr(t):
+    """Device address of a torch tensor (None -> NULL)."""
     if t is None:
-        return ctypes.c_void_p(0)
+        return None
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous device tensor")
-    return ctypes.c_void_p(t.data_ptr())
+    return t.data_ptr()
 
 
 def _i32(a):
-    a = np.ascontiguousarray(a, dtype=np.int32)
-    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    """Host int32 array and its address (the array must stay alive during the call)."""
+    if not (isinstance(a, np.ndarray) and a.dtype == np.int32 and a.flags.c_contiguous):
+        a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.__array_interface__["data"][0]
 
 
-def _stream_ptr(stream) -> ctypes.c_void_p:
+_raw_stream = None
+
+
+def _stream_ptr(stream):
     """torch stream -> hipStream_t; None = torch's current stream (the null stream without a GPU)."""
-    if stream is None:
-        import torch
+    global _raw_stream
+    if stream is not None:
+        return stream.cuda_stream
+    import torch
+    if _raw_stream is None:
         if not torch.cuda.is_available():
-            return ctypes.c_void_p(0)
-        stream = torch.cuda.current_stream()
-    return ctypes.c_void_p(stream.cuda_stream)
+            return None
+        # the raw-handle query skips building a Stream object on every call
+        fast = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        _raw_stream = fast if fast is not None else (lambda dev: torch.cuda.current_stream(dev).cuda_stream)
+    return _raw_stream(torch.cuda.current_device())
 
 
 class Plan:
@@ -213,7 +226,7 @@ class Plan:
         pl, pl_p = _i32(prefix_len)
         bs, bs_p = _i32(block_start)
         if block_table is None:
-            bt_p = ctypes.POINTER(ctypes.c_int32)()
+            bt_p = None
         else:
             bt, bt_p = _i32(block_table)
         if len(cu) != len(pl) + 1 or len(bs) != len(pl):

@@ -21,11 +21,13 @@ constexpr int kWideMinRows = 64;     // (request, kv head) pairs with more query
 constexpr int kNumXcd = 8;  // accelerator dies of an MI355X; workgroup i runs on die i % 8
 // Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
 // scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
-inline double tile_cost_of_rows(int rows) {
-  if (rows <= 16) return 1.0;
-  if (rows <= 64) return 1.1;
-  return 1.2;
+// In tenths, so that costs stay small integers.
+inline int tile_cost10_of_rows(int rows) {
+  if (rows <= 16) return 10;
+  if (rows <= 64) return 11;
+  return 12;
 }
+inline double tile_cost_of_rows(int rows) { return 0.1 * tile_cost10_of_rows(rows); }
 
 // One merge job: `n_splits` partials of the same q tile, stored back to back
 // (`row_count` rows each) starting at workspace row `first_part_row`.
@@ -59,10 +61,10 @@ struct HostPlan {
   int64_t part_rows = 0;            // rows of split-KV partials in the workspace
   size_t workspace_bytes = 0;
   // planner scratch, kept for its capacity
-  std::vector<int32_t> req_first_merge, scratch_order;
+  std::vector<int32_t> req_first_merge, scratch_order, scratch_pos, scratch_count;
   std::vector<int8_t> scratch_lane;
   std::vector<uint64_t> scratch_keys;
-  struct Group { int32_t req, kv_head, kv_begin, kv_end, split, n_splits, n_row_tiles; double cost; };
+  struct Group { int32_t req, kv_head, kv_begin, kv_end, split, n_splits, n_row_tiles, cost10; };  // cost10: tenths of a tile
   std::vector<Group> scratch_groups;
 
   void reset() {

@@ -158,25 +158,39 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
           // cover all n_tiles
           return OPTIMUS_ERR_INVALID_ARGUMENT;
         }
-        const double cost = (double)ceil_div(kv_end - kv_begin, kTileTokens) * tile_cost;
-        groups.push_back({i, g, kv_begin, kv_end, s, n_splits, n_row_tiles, cost});
+        const int32_t cost10 = (int32_t)ceil_div(kv_end - kv_begin, kTileTokens) * tile_cost10_of_rows(rc_max);
+        groups.push_back({i, g, kv_begin, kv_end, s, n_splits, n_row_tiles, cost10});
       }
     n_items += (size_t)n_splits * Hkv * n_row_tiles;
   }
   if (part_rows > (int64_t)INT32_MAX / 2) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  // costliest first; ties keep the emission order for determinism
-  // (sorted as packed integers: inverted cost in tenths of a tile in the high half, emission
-  // index in the low half)
+  // costliest first; ties keep the emission order for determinism.  The cost in tenths of a
+  // tile is a small integer, so this is a stable counting sort (a comparison sort of 2048
+  // groups was half of the planning time); costs beyond the table fall back to sorting packed
+  // integers (inverted cost in the high half, emission index in the low half).
   std::vector<uint64_t>& keys = hp.scratch_keys;
-  keys.resize(groups.size());
-  for (size_t k = 0; k < keys.size(); ++k)
-    keys[k] = ((uint64_t)(0xffffffffu - (uint32_t)std::lround(groups[k].cost * 10.0)) << 32) | (uint64_t)k;
-  std::sort(keys.begin(), keys.end());
   std::vector<int32_t>& order = hp.scratch_order;
   order.resize(groups.size());
-  for (size_t k = 0; k < order.size(); ++k) order[k] = (int32_t)(keys[k] & 0xffffffffu);
+  keys.resize(groups.size());
+  uint32_t cost_max = 0;
+  for (size_t k = 0; k < groups.size(); ++k) {
+    keys[k] = (uint32_t)groups[k].cost10;
+    cost_max = std::max(cost_max, (uint32_t)keys[k]);
+  }
+  constexpr uint32_t kCountingLimit = 1u << 16;
+  if (cost_max < kCountingLimit) {
+    std::vector<int32_t>& first = hp.scratch_count;   // first[b]: output position of bucket b
+    first.assign((size_t)cost_max + 2, 0);
+    for (size_t k = 0; k < groups.size(); ++k) ++first[cost_max - (uint32_t)keys[k] + 1];
+    for (size_t b = 1; b < first.size(); ++b) first[b] += first[b - 1];
+    for (size_t k = 0; k < groups.size(); ++k) order[first[cost_max - (uint32_t)keys[k]]++] = (int32_t)k;
+  } else {
+    for (size_t k = 0; k < keys.size(); ++k) keys[k] = ((uint64_t)(0xffffffffu - (uint32_t)keys[k]) << 32) | (uint64_t)k;
+    std::sort(keys.begin(), keys.end());
+    for (size_t k = 0; k < order.size(); ++k) order[k] = (int32_t)(keys[k] & 0xffffffffu);
+  }
   // deal the groups to the lanes: first pass sizes the lanes, second pass places the items
-  double lane_cost[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
+  int64_t lane_cost[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
   size_t lane_len[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
   std::vector<int8_t>& lane_of = hp.scratch_lane;
   lane_of.resize(groups.size());
@@ -185,17 +199,24 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     for (int x = 1; x < kNumXcd; ++x)
       if (lane_cost[x] < lane_cost[best]) best = x;
     lane_of[gi] = (int8_t)best;
-    lane_cost[best] += groups[gi].cost * groups[gi].n_row_tiles;
+    lane_cost[best] += (int64_t)groups[gi].cost10 * groups[gi].n_row_tiles;
     lane_len[best] += groups[gi].n_row_tiles;
   }
-  // work-list index of depth d in lane x = number of items at smaller (depth, lane): lanes
-  // shorter than d have dropped out of the round-robin
-  auto index_of = [&](int x, size_t d) {
-    size_t idx = 0;
-    for (int y = 0; y < kNumXcd; ++y) idx += std::min(lane_len[y], d);  // full rounds before depth d
-    for (int y = 0; y < x; ++y) idx += lane_len[y] > d ? 1 : 0;        // lanes before x in round d
-    return idx;
-  };
+  // work-list index of depth d in lane x = number of items at smaller (depth, lane); lanes
+  // shorter than d have dropped out of the round-robin.  Tabulated once: lane_pos[x] + d.
+  size_t lane_first[kNumXcd + 1];
+  lane_first[0] = 0;
+  for (int x = 0; x < kNumXcd; ++x) lane_first[x + 1] = lane_first[x] + lane_len[x];
+  std::vector<int32_t>& pos = hp.scratch_pos;   // pos[lane_first[x] + d] = work-list index
+  pos.resize(n_items);
+  {
+    size_t max_len = 0;
+    for (int x = 0; x < kNumXcd; ++x) max_len = std::max(max_len, lane_len[x]);
+    int32_t next = 0;
+    for (size_t d = 0; d < max_len; ++d)
+      for (int x = 0; x < kNumXcd; ++x)
+        if (lane_len[x] > d) pos[lane_first[x] + d] = next++;
+  }
   hp.items.resize(n_items);
   size_t lane_fill[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int32_t gi : order) {
@@ -213,7 +234,7 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
         const MergeItem& m = hp.merges[hp.req_first_merge[gr.req] + gr.kv_head * gr.n_row_tiles + rt];
         it.part_row = m.first_part_row + gr.split * rc;
       }
-      hp.items[index_of(x, lane_fill[x]++)] = it;
+      hp.items[pos[lane_first[x] + lane_fill[x]++]] = it;
     }
   }
   hp.part_rows = part_rows;
