@@ -1072,47 +1072,41 @@ __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
 // Merge of split-KV partials: for each row, M = max_s m_s,
 //   o = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
 // Block (256 threads) = (merge item, group of 16 rows); thread = (row, D/16 columns).
-template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
-  const MergeItem mi = a.merges[blockIdx.x];
+//
+// One pass: the splits are taken KB at a time with every load of a batch (m, l and the
+// partial rows) issued before the first use, and merged online (running maximum M, the sums
+// rescaled when it grows), so a row with up to KB splits costs one memory round trip.
+// Indices past the last split are clamped to it and get weight zero; KB is chosen close to
+// the number of splits so that few loads are such repeats.
+template <int D, int KB>
+__device__ __forceinline__ void merge_splits(const KernelArgs& a, const MergeItem& mi, int rl, int ocol,
+                                             float (&o)[D / 16], float& lt) {
   constexpr int CH = D / 16;
-  const int tid = threadIdx.x;
-  const int rl = blockIdx.y * 16 + (tid >> 4);
-  const int ocol = (tid & 15) * CH;
-  if (rl >= mi.row_count) return;
-  // Splits are taken kMergeBatch at a time with every load of a batch issued before the first
-  // use (indices past the last split are clamped to it and get weight zero), so a row costs
-  // a few memory round trips instead of one per split.
-  constexpr int kMergeBatch = 8;
   const int ns = mi.n_splits;
   const int64_t pr0 = mi.first_part_row + rl;
   float M = -INFINITY;
-  for (int s0 = 0; s0 < ns; s0 += kMergeBatch) {
-    float mv[kMergeBatch];
+  for (int s0 = 0; s0 < ns; s0 += KB) {
+    float mv[KB], lv[KB];
+    f32x4 ov[KB][CH / 4];
 #pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k)
-      mv[k] = a.ws_ml[(pr0 + (int64_t)min(s0 + k, ns - 1) * mi.row_count) * 2];
-#pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k) M = fmaxf(M, mv[k]);
-  }
-  const float Mu = M == -INFINITY ? 0.f : M;
-  float lt = 0.f;
-  float o[CH];
-#pragma unroll
-  for (int c = 0; c < CH; ++c) o[c] = 0.f;
-  for (int s0 = 0; s0 < ns; s0 += kMergeBatch) {
-    float mv[kMergeBatch], lv[kMergeBatch];
-    f32x4 ov[kMergeBatch][CH / 4];
-#pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k) {
+    for (int k = 0; k < KB; ++k) {
       const int64_t pr = pr0 + (int64_t)min(s0 + k, ns - 1) * mi.row_count;
       mv[k] = a.ws_ml[pr * 2];
       lv[k] = a.ws_ml[pr * 2 + 1];
 #pragma unroll
       for (int c = 0; c < CH / 4; ++c) ov[k][c] = *reinterpret_cast<const f32x4*>(a.ws_o + pr * D + ocol + 4 * c);
     }
+    float Mb = M;
 #pragma unroll
-    for (int k = 0; k < kMergeBatch; ++k) {
+    for (int k = 0; k < KB; ++k) Mb = fmaxf(Mb, mv[k]);
+    const float Mu = Mb == -INFINITY ? 0.f : Mb;        // no visible key in any split so far
+    const float keep = fast_exp2(M - Mu);                // M = -inf: 0, and the sums are 0 anyway
+    lt *= keep;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) o[c] *= keep;
+    M = Mb;
+#pragma unroll
+    for (int k = 0; k < KB; ++k) {
       const float w = s0 + k < ns ? fast_exp2(mv[k] - Mu) : 0.f;
       lt = fmaf(w, lv[k], lt);
 #pragma unroll
@@ -1122,6 +1116,24 @@ __global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
       }
     }
   }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
+  const MergeItem mi = a.merges[blockIdx.x];
+  constexpr int CH = D / 16;
+  const int tid = threadIdx.x;
+  const int rl = blockIdx.y * 16 + (tid >> 4);
+  const int ocol = (tid & 15) * CH;
+  if (rl >= mi.row_count) return;
+  float lt = 0.f;
+  float o[CH];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) o[c] = 0.f;
+  if (mi.n_splits <= 2) merge_splits<D, 2>(a, mi, rl, ocol, o, lt);        // uniform per block
+  else if (mi.n_splits <= 4) merge_splits<D, 4>(a, mi, rl, ocol, o, lt);
+  else if (mi.n_splits <= 8) merge_splits<D, 8>(a, mi, rl, ocol, o, lt);
+  else merge_splits<D, 16>(a, mi, rl, ocol, o, lt);
   const float inv = 1.f / lt;
   const int G = a.group;
   const int row = mi.row_begin + rl;
