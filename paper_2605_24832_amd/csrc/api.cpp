@@ -251,7 +251,6 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
   a.merges = reinterpret_cast<const MergeItem*>(d + plan->off_merges);
   a.prefix_len = d + plan->off_prefix;
   a.block_start = d + plan->off_bstart;
-  a.cu_q = d + plan->off_cu_q;
   a.out = out;
   a.ws_o = reinterpret_cast<float*>(workspace);
   a.ws_ml = a.ws_o ? a.ws_o + (size_t)hp.part_rows * p.head_dim : nullptr;

@@ -258,8 +258,13 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
   // ---- Q^T B operands: col r16 = query row, k = d ----
   bf16x8 qreg[NT][KS];
   int vis_end[NT];
-  const int L = a.prefix_len[it.req];
-  const int d_in = L - a.block_start[it.req];
+  // cached length and block offset only matter for the block-causal mask: keep their loads
+  // (which depend on the item's own load) off the start-up path of the plain mode
+  int L = 0, d_in = 0;
+  if (a.mask_mode != 0) {
+    L = a.prefix_len[it.req];
+    d_in = L - a.block_start[it.req];
+  }
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int rl = nt * 16 + r16;
@@ -491,8 +496,13 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
 
   bf16x8 qreg[NT][KS];
   int vis_end[NT];
-  const int L = a.prefix_len[it.req];
-  const int d_in = L - a.block_start[it.req];
+  // cached length and block offset only matter for the block-causal mask: keep their loads
+  // (which depend on the item's own load) off the start-up path of the plain mode
+  int L = 0, d_in = 0;
+  if (a.mask_mode != 0) {
+    L = a.prefix_len[it.req];
+    d_in = L - a.block_start[it.req];
+  }
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int rl = (wave * NT + nt) * 16 + r16;
@@ -787,8 +797,13 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     if (!valid) x = u32x4{0u, 0u, 0u, 0u};
     qreg[s] = __builtin_bit_cast(bf16x8, x);
   }
-  const int L = a.prefix_len[it.req];
-  const int d_in = L - a.block_start[it.req];
+  // cached length and block offset only matter for the block-causal mask: keep their loads
+  // (which depend on the item's own load) off the start-up path of the plain mode
+  int L = 0, d_in = 0;
+  if (a.mask_mode != 0) {
+    L = a.prefix_len[it.req];
+    d_in = L - a.block_start[it.req];
+  }
   const int vis_end = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + jq) / a.block_size + 1) * a.block_size - d_in;
   const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
   const int mask_from = min(it.kv_end, vis_min);
@@ -1062,9 +1077,11 @@ __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
   const optimus_work_item_t it = a.items[blockIdx.x];
   // all row tiles of a (request, kv head) pair with more than kWideMinRows rows take the wide
-  // body, also a narrow last one, so that the siblings run the same schedule side by side
-  const int pair_rows = (a.cu_q[it.req + 1] - a.cu_q[it.req]) * a.group;
-  if (pair_rows > kWideMinRows) wide_tile_body<D, LGP>(a, it, smem);
+  // body, also a narrow last one, so that the siblings run the same schedule side by side.
+  // A later row tile (row_begin > 0) belongs to a pair of more than 128 rows, and the first
+  // one shows min(128, rows): the item alone tells, no further load is needed.
+  static_assert(kWideMinRows < kMaxRowsPerItem, "a first row tile must be able to show it");
+  if (it.row_count > kWideMinRows || it.row_begin > 0) wide_tile_body<D, LGP>(a, it, smem);
   else if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
   else lds_tile_body<D, LGP, 1>(a, it, smem);
 }

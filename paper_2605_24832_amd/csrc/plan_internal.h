@@ -99,7 +99,6 @@ struct KernelArgs {
   int32_t num_q_heads, group, max_pages_per_req, out_fp32;
   int32_t mask_mode, block_size;
   float scale_log2;  // softmax scale * log2(e)
-  const int32_t* cu_q;  // [batch + 1] chunk offsets (the body of an item depends on its pair's rows)
 };
 
 // Kernel launchers (kernels.hip).  `stream` is a hipStream_t.
