@@ -1,0 +1,42 @@
+"""The stored oracle output of the tiny configuration (written by tests/golden/make_golden.py,
+which calls only the oracle): the oracle must keep reproducing it, and the HIP path must match
+it without the oracle being run at all."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from tests.golden import make_golden
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def load():
+    with open(os.path.join(HERE, "golden", "tiny_config0.json")) as f:
+        return json.load(f)
+
+
+def test_oracle_reproduces_the_stored_output(oracle_mod):
+    doc = load()
+    w, out, digest = make_golden.compute()
+    assert digest == doc["inputs_sha256"], "the seeded CPU input generator no longer produces the stored inputs"
+    for row in doc["rows"]:
+        ref = np.array([float(x) for x in row["values"]])
+        np.testing.assert_allclose(out[row["token"], row["head"]], ref, rtol=1e-12, atol=1e-15)
+    assert abs(out.sum() - float(doc["sum_of_all_outputs"])) < 1e-9
+
+
+@pytest.mark.gpu
+def test_hip_path_matches_the_stored_output():
+    import torch
+    from paper_2605_24832_amd import inputs
+    from tests import hip_path as hp
+    doc = load()
+    w = hp.clone_workload(inputs.make_config(0, device="cpu"), device="cuda:0")
+    out, _ = hp.run_hip(w)
+    got = out.float().cpu().numpy().astype(np.float64)
+    for row in doc["rows"]:
+        ref = np.array([float(x) for x in row["values"]])
+        assert np.abs(got[row["token"], row["head"]] - ref).max() <= 1e-2
+    assert abs(got.sum() - float(doc["sum_of_all_outputs"])) < 1e-3 * got.size
