@@ -137,6 +137,17 @@ def measure(cfg: int, chunk, steps: int, warmup: int, device: str):
     return w, r, res
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, runner, budget_s: float = 15.0):
     """Time the fp64 oracle on a bounded sample of the same workload and check the GPU
     output of those requests against it."""
@@ -183,7 +194,7 @@ def cpu_baseline(w, runner, budget_s: float = 15.0):
     err = np.abs(gpu_out[tok] - ref)
     return {
         "value": float(len(tok) / dt), "unit": "tokens/s", "cores": int(oracle.num_threads()),
-        "kind": "oracle",
+        "kind": "oracle", "cpu_model": cpu_model(),
         "sample": f"requests 0..{n - 1} of {w.name} ({len(tok)} of {w.total_q} query tokens, "
                   f"{dt:.2f} s of fp64 CPU work)",
     }, {"max_abs_err": float(err.max()), "mean_abs_err": float(err.mean()),
@@ -418,7 +429,10 @@ def main():
         "roofline": roofline,
         "attention_tflops": res["tflops"], "achieved_hbm_TBs": res["hbm_GBs"] / 1e3,
         "ms_per_step_plan_excluded": res["ms_per_step_plan_excluded"],
+        "tokens_per_s_plan_excluded": res["query_tokens"] / (res["ms_per_step_plan_excluded"] * 1e-3),
         "plan_update_host_ms": res["plan_update_host_ms"],
+        # one exponential per (query row, visible key): co-critical with the MFMA work at large chunks
+        "exp_count_per_launch": res["flops"] // (4 * w.head_dim),
         "work_items": res["work_items"], "merge_items": res["merge_items"],
     }
     if not args.no_cpu_baseline:
