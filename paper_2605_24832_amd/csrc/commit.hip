@@ -51,7 +51,8 @@ __global__ __launch_bounds__(kScanThreads) void commit_scan_kernel(
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int base = base0 + u * kStep;
-      raw[u] = base < hi ? *reinterpret_cast<const u32x4c*>(row + base) : u32x4c{0u, 0u, 0u, 0u};
+      raw[u] = base < hi ? __builtin_nontemporal_load(reinterpret_cast<const u32x4c*>(row + base))   // read once
+                        : u32x4c{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
