@@ -760,24 +760,40 @@ constexpr int wide_smem_floats() { return kWideStages * 2 * (D * 4) * 4; }
 // body below waits for them by hand, and a compiler-inserted wait for one of its own loads
 // only waits longer than needed (the counter retires in order).  M0 holds the LDS address
 // (one wait state between the scalar write of M0 and its use).
+// STREAM adds the non-temporal hint (for tiles no other workgroup reads).
+template <bool STREAM>
 __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
+                 :
+                 : "v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
 }
 
 // Same with a wave-uniform base address in scalar registers plus a 32-bit lane offset: no
 // vector address arithmetic per load.
+template <bool STREAM>
 __device__ __forceinline__ void load_to_lds_16(const void* base_uniform, uint32_t lane_offset,
                                                uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(lane_offset), "s"(base_uniform), "s"(lds_addr)
-               : "memory", "m0");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(lane_offset), "s"(base_uniform), "s"(lds_addr)
+                 : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(base_uniform), "s"(lds_addr)
+                 : "memory", "m0");
 }
 
-template <int D, int LGP>
+// STREAM: the pair has a single row tile, so nobody else reads its K/V in this launch.
+template <int D, int LGP, bool STREAM>
 __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimus_work_item_t& it,
                                                float* smem) {
   constexpr int KS = D / 16, DB = D / 32, P = 1 << LGP;
@@ -885,15 +901,15 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     if constexpr (LGP == 4) {   // two pages per tile: the page differs between lanes
 #pragma unroll
       for (int i = 0; i < LPT; ++i)
-        load_to_lds_16((second_page[i][0] ? k1 : k0) + ksrc[i], dst + 16u * (256 * i));
+        load_to_lds_16<STREAM>((second_page[i][0] ? k1 : k0) + ksrc[i], dst + 16u * (256 * i));
 #pragma unroll
       for (int i = 0; i < LPT; ++i)
-        load_to_lds_16((second_page[i][1] ? v1 : v0) + vsrc[i], dst + 16u * (PIECES + 256 * i));
+        load_to_lds_16<STREAM>((second_page[i][1] ? v1 : v0) + vsrc[i], dst + 16u * (PIECES + 256 * i));
     } else {
 #pragma unroll
-      for (int i = 0; i < LPT; ++i) load_to_lds_16(k0, ksrc[i], dst + 16u * (256 * i));
+      for (int i = 0; i < LPT; ++i) load_to_lds_16<STREAM>(k0, ksrc[i], dst + 16u * (256 * i));
 #pragma unroll
-      for (int i = 0; i < LPT; ++i) load_to_lds_16(v0, vsrc[i], dst + 16u * (PIECES + 256 * i));
+      for (int i = 0; i < LPT; ++i) load_to_lds_16<STREAM>(v0, vsrc[i], dst + 16u * (PIECES + 256 * i));
     }
   };
   // S^T of item tile t: register v of a lane is key 32*tile + 16*(v/8) + 8h + v%8, row r32
@@ -1088,7 +1104,11 @@ __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
   // A later row tile (row_begin > 0) belongs to a pair of more than 128 rows, and the first
   // one shows min(128, rows): the item alone tells, no further load is needed.
   static_assert(kWideMinRows < kMaxRowsPerItem, "a first row tile must be able to show it");
-  if (it.row_count > kWideMinRows || it.row_begin > 0) wide_tile_body<D, LGP>(a, it, smem);
+  if (it.row_count > kWideMinRows || it.row_begin > 0) {
+    // a first row tile of fewer than 128 rows is the pair's only one: its K/V are read once
+    if (it.row_begin == 0 && it.row_count < kMaxRowsPerItem) wide_tile_body<D, LGP, true>(a, it, smem);
+    else wide_tile_body<D, LGP, false>(a, it, smem);
+  }
   else if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
   else lds_tile_body<D, LGP, 1>(a, it, smem);
 }
