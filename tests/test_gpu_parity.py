@@ -95,7 +95,7 @@ def test_gqa7_many_q_tiles(oracle_mod):
     full_parity(oracle_mod, w, "gqa7")
 
 
-@pytest.mark.parametrize("Hq,Hkv,D,P", [(12, 2, 128, 16), (32, 2, 64, 32), (16, 1, 128, 64)])
+@pytest.mark.parametrize("Hq,Hkv,D,P", [(12, 2, 128, 16), (32, 2, 64, 32), (16, 1, 128, 64), (24, 2, 64, 16)])
 def test_wide_row_tiles(oracle_mod, Hq, Hkv, D, P):
     """Every lds-tile class: 33..64, 65..128, 129..192, 193..256 rows and more than 256 rows
     (several row tiles), unsplit and split, with ragged key tails."""
