@@ -150,7 +150,8 @@ int32_t optimus_attn_plan_get_work_items(const optimus_attn_plan_t* plan,
                                          optimus_work_item_t* items_out, int32_t capacity);
 
 /* Planner knobs (host).  target_items: aim for at least this many work items
- * (0 = default: a multiple of the device's compute-unit count).
+ * (0 = default: the list is fitted to whole rounds of the workgroups that are
+ * resident at once, two per compute unit).
  * min_split_tokens / max_split_tokens: bounds on the keys one work item scans
  * (multiples of 32; 0 = default).                                               */
 int optimus_attn_plan_set_tuning(optimus_attn_plan_t* plan, int32_t target_items,

@@ -1107,8 +1107,8 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 //
 template <int D, int LGP>
 __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
-  constexpr int kFloats0 = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
-                               ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
+  constexpr int kFloats0 = split_wave_smem_floats<D, 2>() > lds_tile_smem_floats<D>()
+                               ? split_wave_smem_floats<D, 2>() : lds_tile_smem_floats<D>();
   constexpr int kFloats = kFloats0 > wide_smem_floats<D>() ? kFloats0 : wide_smem_floats<D>();
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
   const optimus_work_item_t it = a.items[blockIdx.x];
@@ -1123,6 +1123,9 @@ __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
     else wide_tile_body<D, LGP, false>(a, it, smem);
   }
   else if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
+#ifdef OPT_SPLIT2
+  else if (it.row_count <= 32) split_wave_body<D, LGP, 2>(a, it, smem);
+#endif
   else lds_tile_body<D, LGP, 1>(a, it, smem);
 }
 

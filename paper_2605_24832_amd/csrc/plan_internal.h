@@ -17,15 +17,24 @@ constexpr int kWavesPerBlock = 4;
 // keys), 17..128 rows the lds-tile body with 1..2 subtiles per wave (the waves split the
 // rows).  A (request, kv head) pair with more rows is cut into row tiles of 128.
 constexpr int kMaxRowsPerItem = 128;
-constexpr int kWideMinRows = 64;     // (request, kv head) pairs with more query rows take the wide body
+#ifndef OPT_WIDE_MIN_ROWS
+#define OPT_WIDE_MIN_ROWS 64
+#endif
+constexpr int kWideMinRows = OPT_WIDE_MIN_ROWS;     // (request, kv head) pairs with more query rows take the wide body
 constexpr int kNumXcd = 8;  // accelerator dies of an MI355X; workgroup i runs on die i % 8
 // Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
 // scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
 // In tenths, so that costs stay small integers.
 inline int tile_cost10_of_rows(int rows) {
+#ifndef OPT_COST_MID
+#define OPT_COST_MID 11
+#endif
+#ifndef OPT_COST_WIDE
+#define OPT_COST_WIDE 12
+#endif
   if (rows <= 16) return 10;
-  if (rows <= 64) return 11;
-  return 12;
+  if (rows <= 64) return OPT_COST_MID;
+  return OPT_COST_WIDE;
 }
 inline double tile_cost_of_rows(int rows) { return 0.1 * tile_cost10_of_rows(rows); }
 
@@ -66,6 +75,13 @@ struct HostPlan {
   std::vector<uint64_t> scratch_keys;
   struct Group { int32_t req, kv_head, kv_begin, kv_end, split, n_splits, n_row_tiles, cost10; };  // cost10: tenths of a tile
   std::vector<Group> scratch_groups;
+  // per request with a non-empty chunk: key tiles, cost of a tile in tenths (and its
+  // reciprocal), bounds of the tiles per item, items per key range (kv heads x row tiles)
+  struct Shapes {
+    std::vector<double> tiles, w10, inv_w10, lo, hi, mult;
+    void clear() { tiles.clear(); w10.clear(); inv_w10.clear(); lo.clear(); hi.clear(); mult.clear(); }
+  };
+  Shapes scratch_shapes;
 
   void reset() {
     batch = 0; total_q = 0; part_rows = 0; workspace_bytes = 0;

@@ -85,22 +85,88 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   }
 
   // ---- how many keys one work item scans ----
-  double total_cost = 0.0;
+  // Every (request, kv head) pair is cut into equal key ranges of at most `tpi` tiles, with
+  // tpi = ceil(item_cost / tile cost of the pair's row count), clamped; item_cost (tenths of
+  // a split-wave tile) is the one free parameter.
+  const int64_t min_tiles =
+      std::max<int64_t>(1, (tuning.min_split_tokens > 0 ? tuning.min_split_tokens : 256) / kTileTokens);
+  const int64_t max_tiles = std::max<int64_t>(
+      min_tiles, tuning.max_split_tokens > 0 ? tuning.max_split_tokens / kTileTokens : (int64_t)1 << 40);
+  HostPlan::Shapes& sh = hp.scratch_shapes;
+  sh.clear();
+  double total10 = 0.0;
   for (int i = 0; i < batch; ++i) {
     const int64_t c = cu_q[i + 1] - cu_q[i];
     if (c == 0) continue;
     const int64_t rows = c * G;
-    const int64_t tiles = ceil_div((int64_t)prefix_len[i] + c, kTileTokens);
-    for (int64_t r0 = 0; r0 < rows; r0 += kMaxRowsPerItem)
-      total_cost += (double)Hkv * tiles *
-                    tile_cost_of_rows((int)std::min<int64_t>(kMaxRowsPerItem, rows - r0));
+    const int rc_max = (int)std::min<int64_t>(kMaxRowsPerItem, rows);
+    const double tiles = (double)ceil_div((int64_t)prefix_len[i] + c, kTileTokens);
+    const double w10 = tile_cost10_of_rows(rc_max);
+    // a split costs one partial (rows x (D+2) floats written, then read by the merge): keep
+    // it well below the K/V bytes the item streams (32 keys x 2 x D bf16 per tile)
+    const double lo = (double)std::max<int64_t>(min_tiles, (rc_max + 7) / 8);
+    const double mult = (double)(Hkv * ceil_div(rows, kMaxRowsPerItem));
+    sh.tiles.push_back(tiles); sh.w10.push_back(w10); sh.inv_w10.push_back(1.0 / w10);
+    sh.lo.push_back(lo); sh.hi.push_back((double)std::max<int64_t>(max_tiles, (int64_t)lo));
+    sh.mult.push_back(mult);
+    total10 += mult * tiles * w10;
   }
-  const int64_t target_items = tuning.target_items > 0 ? tuning.target_items : 4 * (int64_t)num_cus;
-  const int64_t min_tiles =
-      std::max<int64_t>(1, (tuning.min_split_tokens > 0 ? tuning.min_split_tokens : 256) / kTileTokens);
-  const int64_t max_tiles = std::max<int64_t>(
-      min_tiles, (tuning.max_split_tokens > 0 ? tuning.max_split_tokens : 8192) / kTileTokens);
-  const double target_cost = total_cost / (double)std::max<int64_t>(target_items, 1);
+  // the tiles-per-item rule, the same expression here and where the items are emitted
+  auto tiles_per_item_of = [](double item_cost10, double inv_w10, double lo, double hi) {
+    return std::min(hi, std::max(lo, std::ceil(item_cost10 * inv_w10)));
+  };
+  struct Fit { double n_items, cost_min, cost_max; };
+  auto evaluate = [&](double item_cost10) {
+    Fit f{0.0, 1e300, 0.0};
+    const size_t n = sh.tiles.size();
+    for (size_t k = 0; k < n; ++k) {
+      const double tpi = tiles_per_item_of(item_cost10, sh.inv_w10[k], sh.lo[k], sh.hi[k]);
+      const double ns = std::ceil(sh.tiles[k] / tpi);
+      const double tps = std::ceil(sh.tiles[k] / ns);
+      f.n_items += ns * sh.mult[k];
+      f.cost_max = std::max(f.cost_max, tps * sh.w10[k]);
+      f.cost_min = std::min(f.cost_min, (sh.tiles[k] - (ns - 1.0) * tps) * sh.w10[k]);
+    }
+    return f;
+  };
+  // Two workgroups are resident per CU, so `slots` items run at once.  Measured on mixed and
+  // uniform batches: a list that fills the slots exactly once beats every finer cut when its
+  // items are balanced (a second, partly filled round costs its whole length, and every
+  // item pays a few microseconds of start-up), and a list slightly longer than a multiple of
+  // the slots is the worst case.  So for lists of up to two rounds the item cost is fitted:
+  // for k and k+1 rounds (k the fewest possible) take the smallest item cost whose list has
+  // at most k * slots items, and keep the k whose estimated time is lower: one round lasts
+  // as long as its longest item; several rounds last total / slots plus, as the drain at the
+  // end of a costliest-first list, about one of the smallest items.
+  const double slots = 2.0 * std::max(num_cus, 1);
+  const double kItemOverhead10 = 40.0;   // start-up of an item in tenths of a tile (about 4 us)
+  double item_cost10;
+  if (tuning.target_items > 0) {
+    item_cost10 = total10 / (double)tuning.target_items;
+  } else {
+    const Fit uncut = evaluate(1e300);
+    if (uncut.n_items > 2.0 * slots) {
+      item_cost10 = total10 / (2.0 * slots);
+    } else {
+      const double k_min = std::max(1.0, std::ceil(uncut.n_items / slots));
+      double best_time = 1e300;
+      item_cost10 = 1e300;
+      for (double k = k_min; k <= k_min + 1.0; k += 1.0) {
+        // smallest cost with at most k * slots items: the count falls as the cost grows
+        double lo = total10 / (k * slots) * 0.5, hi = std::max(uncut.cost_max, lo);
+        if (evaluate(lo).n_items <= k * slots) hi = lo;
+        for (int it = 0; it < 14 && hi - lo > 0.5; ++it) {
+          const double mid = 0.5 * (lo + hi);
+          if (evaluate(mid).n_items <= k * slots) hi = mid; else lo = mid;
+        }
+        const Fit f = evaluate(hi);
+        const double time = f.n_items <= slots
+                                ? f.cost_max + kItemOverhead10
+                                : (total10 + f.n_items * kItemOverhead10) / slots + f.cost_min + kItemOverhead10;
+        if (time < best_time) { best_time = time; item_cost10 = hi; }
+      }
+    }
+  }
 
   // ---- sibling groups ----
   // A group = the row tiles of one (request, kv head, key range): same K/V stream, same
@@ -115,6 +181,7 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   int64_t part_rows = 0;
   size_t n_items = 0;
   hp.req_first_merge.assign(batch, -1);
+  size_t shape_k = 0;   // index into sh: one entry per request with a non-empty chunk
   for (int i = 0; i < batch; ++i) {
     const int c = cu_q[i + 1] - cu_q[i];
     if (c == 0) continue;
@@ -124,13 +191,8 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
     const int n_row_tiles = (int)ceil_div(rows, kMaxRowsPerItem);
     // all row tiles of a pair use the split of the widest one, so that their key ranges match
     const int rc_max = std::min(kMaxRowsPerItem, rows);
-    const double tile_cost = tile_cost_of_rows(rc_max);
-    // a split costs one partial (rows x (D+2) floats written, then read by the merge): keep
-    // it well below the K/V bytes the item streams (32 keys x 2 x D bf16 per tile)
-    const int64_t min_tiles_rows = std::max<int64_t>(min_tiles, (rc_max + 7) / 8);
-    const int64_t tiles_per_item =
-        std::min(std::max(max_tiles, min_tiles_rows),
-                 std::max(min_tiles_rows, (int64_t)std::ceil(target_cost / tile_cost)));
+    const int64_t tiles_per_item = (int64_t)tiles_per_item_of(item_cost10, sh.inv_w10[shape_k], sh.lo[shape_k], sh.hi[shape_k]);
+    ++shape_k;
     const int n_splits = (int)ceil_div(n_tiles, tiles_per_item);
     const int tiles_per_split = (int)ceil_div(n_tiles, n_splits);
     if (n_splits > 1) {
