@@ -179,6 +179,47 @@ def test_work_list_with_forced_tuning_and_odd_shapes():
         plan.set_tuning(min_split_tokens=33)
 
 
+def test_default_plan_fills_whole_rounds_of_resident_workgroups():
+    """Short lists are fitted to the 512 workgroup slots of a 256-CU device (the host-only
+    plan assumes 256 CUs): at most one full round when a balanced one exists, never a
+    little more than a multiple of 512; an explicit target_items switches the fit off."""
+    slots = 512
+    # config-2-like mix: 256 (request, kv head) pairs, 352 unsplit items -> one round
+    p = make_params(num_q_heads=28, num_kv_heads=4)
+    rng = np.random.RandomState(11)
+    for R in (24, 32, 48, 64):
+        L = rng.randint(512, 4097, size=R)
+        c = rng.choice([1, 2, 4, 8, 16, 32], size=R)
+        cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+        plan = Plan(p, device=-1)
+        plan.plan_update(cu, L, L)
+        n = plan.num_work_items()
+        assert 0.8 * slots <= n <= slots, (R, n)
+        coverage_check(plan, p, cu, L)
+        plan.set_tuning(target_items=1024)
+        plan.plan_update(cu, L, L)
+        assert plan.num_work_items() > slots
+    # long-context case: 4 requests x 8 kv heads x 4 row tiles of 128 rows -> 4 splits = 512
+    p = make_params(num_q_heads=32, num_kv_heads=8, page_size=64, block_size=128, max_pages_per_req=520)
+    L = np.full(4, 32768)
+    c = np.full(4, 128)
+    cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    plan = Plan(p, device=-1)
+    plan.plan_update(cu, L, L)
+    assert plan.num_work_items() == slots
+    coverage_check(plan, p, cu, L)
+    # 512 unsplit pairs of very different lengths: one round would be unbalanced, so two
+    p = make_params(num_q_heads=32, num_kv_heads=8)
+    rng = np.random.RandomState(12)
+    L = rng.randint(1024, 8193, size=64)
+    c = rng.choice([1, 2, 4], size=64)
+    cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    plan = Plan(p, device=-1)
+    plan.plan_update(cu, L, L)
+    assert slots < plan.num_work_items() <= 2 * slots
+    coverage_check(plan, p, cu, L)
+
+
 def test_plan_is_deterministic_and_longest_first_within_class():
     p = make_params(num_q_heads=32, num_kv_heads=4)
     rng = np.random.RandomState(5)
