@@ -573,9 +573,10 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   }
 
   u32x4 rk[PF][LPT], rv[PF][LPT];
-  auto LOAD = [&](int set, int t) {   // tile t of the item -> registers
+  // page ids of item tile t (clamped to the item's last tile)
+  auto PAGES = [&](int t) { return tile_pages<LGP>(bt, tile_lo + t, tile_lo + n - 1, last_page); };
+  auto LOAD = [&](int set, int t, TilePages pg) {   // tile t of the item -> registers
     const int tile = tile_lo + t;
-    const TilePages pg = tile_pages<LGP>(bt, tile, tile_lo + n - 1, last_page);
     if constexpr (LGP == 4) {
 #pragma unroll
       for (int i = 0; i < LPT; ++i) {
@@ -640,9 +641,12 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   constexpr int UNROLL = (PF % 2 == 0) ? PF : 2 * PF;
 #pragma unroll
   for (int s0 = 0; s0 < PF; ++s0)
-    if (s0 < n) LOAD(s0, s0);
+    if (s0 < n) LOAD(s0, s0, PAGES(s0));
   STORE(0, 0);
-  if (PF < n) LOAD(0, PF);
+  if (PF < n) LOAD(0, PF, PAGES(PF));
+  // Page ids are fetched one iteration before the loads that use them: asked for right before
+  // its use, the (scalar) load's latency would be paid in every iteration.
+  TilePages pg_next = PAGES(PF + 1);
   __syncthreads();
   // Steady state without a branch between the issue of a tile's loads and their use, so the
   // memory-counter waits the compiler inserts are exact (a conditional load makes it wait for
@@ -654,7 +658,8 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
     for (int u = 0; u < UNROLL; ++u) {
       COMPUTE(u & 1, t + u);
       STORE((u + 1) & 1, (u + 1) % PF);
-      LOAD((u + 1) % PF, t + u + 1 + PF);
+      LOAD((u + 1) % PF, t + u + 1 + PF, pg_next);
+      pg_next = PAGES(t + u + 2 + PF);
       __syncthreads();
     }
   }
@@ -664,7 +669,8 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
       if (t + u >= n) break;
       COMPUTE(u & 1, t + u);
       if (t + u + 1 < n) STORE((u + 1) & 1, (u + 1) % PF);
-      if (t + u + 1 + PF < n) LOAD((u + 1) % PF, t + u + 1 + PF);
+      if (t + u + 1 + PF < n) LOAD((u + 1) % PF, t + u + 1 + PF, pg_next);
+      pg_next = PAGES(t + u + 2 + PF);
       __syncthreads();
     }
   }
