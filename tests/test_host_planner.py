@@ -220,6 +220,73 @@ def test_default_plan_fills_whole_rounds_of_resident_workgroups():
     coverage_check(plan, p, cu, L)
 
 
+def interval_coverage_check(plan, p: AttnParams, cu_q, prefix_len):
+    """coverage_check without the dense matrix (for long contexts): per (request, kv head) the
+    row tiles partition the rows, and the key ranges of every row tile partition [0, kv_len)."""
+    items = plan.work_items()
+    G = p.num_q_heads // p.num_kv_heads
+    c = np.diff(cu_q)
+    assert (items["kv_begin"] % 32 == 0).all() and (items["kv_begin"] < items["kv_end"]).all()
+    order = np.lexsort((items["kv_begin"], items["row_begin"], items["kv_head"], items["req"]))
+    it = items[order]
+    n_expected_groups = 0
+    k = 0
+    for i in range(len(prefix_len)):
+        if c[i] == 0:
+            continue
+        rows, kv_len = int(c[i]) * G, int(prefix_len[i] + c[i])
+        for g in range(p.num_kv_heads):
+            r0 = 0
+            while r0 < rows:
+                rc = min(128, rows - r0)
+                pos = 0
+                first = k
+                while k < len(it) and (it["req"][k], it["kv_head"][k], it["row_begin"][k]) == (i, g, r0):
+                    assert it["row_count"][k] == rc and it["kv_begin"][k] == pos
+                    assert it["q_token0"][k] == cu_q[i]
+                    pos = int(it["kv_end"][k])
+                    k += 1
+                assert pos == kv_len, f"request {i} head {g} rows {r0}: keys end at {pos}, not {kv_len}"
+                n_split = k - first
+                assert ((it["part_row"][first:k] >= 0).all() if n_split > 1 else it["part_row"][first] == -1)
+                r0 += rc
+                n_expected_groups += 1
+    assert k == len(it)
+    parts = np.sort(items["part_row"][items["part_row"] >= 0])
+    assert len(np.unique(parts)) == len(parts)
+    return items
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_batches_are_covered_and_lists_stay_short(seed):
+    """Seeded random geometries and batches, default tuning: exact coverage, and the fitted
+    list never exceeds what the plain rule would give by more than the per-pair rounding."""
+    rng = np.random.RandomState(4000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 7, 8]))
+    B = int(rng.choice([32, 64, 128]))
+    P = int(rng.choice([16, 64]))
+    R = int(rng.choice([1, 2, 5, 17, 64, 200, 400]))
+    Lmax = int(rng.choice([300, 5000, 40000, 1000000]))
+    p = make_params(num_q_heads=Hkv * G, num_kv_heads=Hkv, block_size=B, page_size=P,
+                    max_pages_per_req=(Lmax + B) // P + 2, num_pages=1 << 30)
+    d_in = rng.randint(0, B, size=R)
+    c = np.array([rng.randint(0, B - d + 1) for d in d_in])
+    L = rng.randint(0, Lmax // B + 1, size=R) * B + d_in
+    cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+    plan = Plan(p, device=-1)
+    plan.plan_update(cu, L, L - d_in)
+    items = interval_coverage_check(plan, p, cu, L)
+    n_pairs_tiles = int(sum(Hkv * -(-int(ci) * G // 128) for ci in c if ci > 0))
+    assert len(items) >= n_pairs_tiles
+    # never more than two rounds of 512 plus one item per row tile, unless unsplit is already more
+    assert len(items) <= max(2 * 512 + n_pairs_tiles, n_pairs_tiles)
+    if len(items) > n_pairs_tiles:   # something was split: splits respect the 256-key minimum
+        split = items[items["part_row"] >= 0]
+        full = split[split["kv_end"] % 32 == 0]
+        assert ((full["kv_end"] - full["kv_begin"]) >= 32).all()
+
+
 def test_plan_is_deterministic_and_longest_first_within_class():
     p = make_params(num_q_heads=32, num_kv_heads=4)
     rng = np.random.RandomState(5)
