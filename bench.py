@@ -288,6 +288,31 @@ def measure_reorg(device: str, steps: int = 50):
             "parity_vs_oracle": {"identical": bool(same)}}
 
 
+def measure_mfma_probe(device: str):
+    """What the matrix cores deliver on this machine, as context for the MFMA-bound rows: the
+    library's bf16 GEMM (torch.matmul, 8192^3) on N(0,1) data and on zeros.  The rate depends
+    on the data (power management lowers the clock under random operands), and so does the
+    attention kernel's."""
+    import torch
+    n = 8192
+    g = torch.Generator(device=device).manual_seed(7)
+    a = torch.randn(n, n, device=device, dtype=torch.bfloat16, generator=g)
+    b = torch.randn(n, n, device=device, dtype=torch.bfloat16, generator=g)
+    out = {"workload": "torch.matmul bf16 8192 x 8192 x 8192 (library GEMM)"}
+    for tag, x, y in (("random_n01_tflops", a, b), ("zeros_tflops", torch.zeros_like(a), torch.zeros_like(b))):
+        for _ in range(5):
+            x @ y
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            x @ y
+        e1.record()
+        torch.cuda.synchronize()
+        out[tag] = 2.0 * n ** 3 / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
+    return out
+
+
 def measure_selector(device: str):
     """Chunk-size selection (Sec. 5) fed by this machine's own profile: one decoder layer's step
     latency over batch x chunk = the attention step of this library (prefix 1024 per request,
@@ -467,6 +492,7 @@ def main():
             del w2, r2
             torch.cuda.empty_cache()
         line["other_configs"] = others
+        line["mfma_probe"] = measure_mfma_probe(dev)
         line["next_rows"] = {"commit_step": measure_commit(dev), "reorg_step": measure_reorg(dev),
                              "chunk_selector": measure_selector(dev)}
     line["paper_context"] = ("the paper reports no kernel-level number for this path; its system "
