@@ -4,6 +4,7 @@
 // turns them into a flat list of device work items.  Pure host code.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 
 #include "plan_internal.h"
 
@@ -208,9 +209,8 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
           part_rows += (int64_t)n_splits * rc;
         }
     }
-    // emission order (request, kv head, split): with equal costs the dealing below then
-    // spreads the kv heads of a request over the XCDs instead of pinning head x to XCD x
-    // (measured a few percent faster: the heads sit at fixed offsets inside every page)
+    // emission order (request, kv head, split); the dealing below rotates its tie-break so
+    // that the kv heads of a request spread over the XCDs
     for (int g = 0; g < Hkv; ++g)
       for (int s = 0; s < n_splits; ++s) {
         const int kv_begin = s * tiles_per_split * kTileTokens;
@@ -257,9 +257,17 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   std::vector<int8_t>& lane_of = hp.scratch_lane;
   lane_of.resize(groups.size());
   for (int32_t gi : order) {
-    int best = 0;
-    for (int x = 1; x < kNumXcd; ++x)
+    // Ties go to the first lane at or after (request + split) mod 8.  With a fixed first lane
+    // the kv heads of every request (equal costs, dealt one after the other) would land on
+    // the same lanes again and again, i.e. XCD x would read only head x of every page: one
+    // 4 KB-aligned slice of the address space per XCD (no difference measured on the
+    // high-load configuration, where it happens; kept so that no layout can make it matter).
+    const int first = (groups[gi].req + groups[gi].split) & (kNumXcd - 1);
+    int best = first;
+    for (int k = 1; k < kNumXcd; ++k) {
+      const int x = (first + k) & (kNumXcd - 1);
       if (lane_cost[x] < lane_cost[best]) best = x;
+    }
     lane_of[gi] = (int8_t)best;
     lane_cost[best] += (int64_t)groups[gi].cost10 * groups[gi].n_row_tiles;
     lane_len[best] += groups[gi].n_row_tiles;
