@@ -12,6 +12,10 @@
  * attains it.  A position is committed iff confidence > threshold.  Optional
  * progress rule: a request that has chunk tokens but none above the threshold
  * commits its single most confident one (first on ties) when min_commit = 1.
+ * A logit that is -inf or NaN stands for a vocabulary entry that cannot be
+ * chosen (a masked entry): it can never be the token and adds nothing to the
+ * softmax sum.  A row without any other entry has confidence 0 and token 0.
+ * +inf logits are outside the definition.
  */
 #include <math.h>
 #include <stdint.h>
@@ -22,6 +26,12 @@ static double bf16_to_double_c(uint16_t b) {
   float f;
   memcpy(&f, &u, sizeof f);
   return (double)f;
+}
+
+/* value of a logit; masked entries (NaN, -inf) read as -inf */
+static double logit_value(uint16_t b) {
+  const double x = bf16_to_double_c(b);
+  return isnan(x) ? -INFINITY : x;
 }
 
 /* logits: bf16 [T, row_stride], first `vocab` entries of a row are used.
@@ -36,11 +46,20 @@ int oracle_commit(int32_t num_tokens, int32_t vocab, int64_t row_stride, const u
     double mx = -INFINITY;
     int arg = 0;
     for (int v = 0; v < vocab; ++v) {
-      double x = bf16_to_double_c(row[v]);
+      double x = logit_value(row[v]);
       if (x > mx) { mx = x; arg = v; }
     }
+    if (mx == -INFINITY) {          /* every entry masked */
+      token_out[t] = 0;
+      conf_out[t] = 0.0;
+      commit_out[t] = 0;
+      continue;
+    }
     double z = 0.0;
-    for (int v = 0; v < vocab; ++v) z += exp(bf16_to_double_c(row[v]) - mx);
+    for (int v = 0; v < vocab; ++v) {
+      const double x = logit_value(row[v]);
+      if (x != -INFINITY) z += exp(x - mx);
+    }
     token_out[t] = arg;
     conf_out[t] = 1.0 / z;          /* exp(mx - mx) / z */
     commit_out[t] = conf_out[t] > threshold ? 1 : 0;

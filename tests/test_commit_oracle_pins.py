@@ -79,3 +79,47 @@ def test_progress_rule_commits_the_most_confident_token(oracle_mod):
     y = torch.zeros(4, V)
     _, _, com3 = oracle_mod.commit(bits(y), V, 0.9, [0, 4], 1)
     np.testing.assert_array_equal(com3, [1, 0, 0, 0])
+
+
+def test_masked_entries_add_nothing(oracle_mod):
+    """-inf (and NaN) logits are entries that cannot be chosen: aligned runs of them before the
+    first finite entry, between finite entries and at the end leave exactly the softmax over
+    the finite entries (torch.softmax gives -inf entries probability 0)."""
+    V = 64
+    g = torch.Generator().manual_seed(11)
+    x = torch.randn(6, V, generator=g).to(torch.bfloat16).float()
+    x[0, :16] = float("-inf")                    # two whole 8-entry pieces masked before any finite entry
+    x[1, 8:40] = float("-inf")
+    x[2, 48:] = float("-inf")
+    x[3, :63] = float("-inf")                    # a single finite entry: confidence 1, token 63
+    x[4, ::2] = float("-inf")
+    x[5, :] = float("-inf")                      # nothing can be chosen
+    tok, conf, com = oracle_mod.commit(bits(x), V, 0.9)
+    p = torch.softmax(x[:5].double(), dim=-1)
+    np.testing.assert_allclose(conf[:5], p.max(dim=-1).values.numpy(), rtol=1e-13)
+    np.testing.assert_array_equal(tok[:5], p.argmax(dim=-1).numpy())
+    assert tok[3] == 63 and conf[3] == 1.0 and com[3] == 1
+    assert tok[5] == 0 and conf[5] == 0.0 and com[5] == 0
+    # NaN reads as -inf: same outputs bit for bit
+    y = x.clone()
+    y[torch.isinf(y)] = float("nan")
+    tok2, conf2, com2 = oracle_mod.commit(bits(y), V, 0.9)
+    np.testing.assert_array_equal(tok2, tok)
+    np.testing.assert_array_equal(conf2, conf)
+    np.testing.assert_array_equal(com2, com)
+
+
+def test_progress_rule_with_one_token_requests_and_masked_rows(oracle_mod):
+    """A one-token request always commits its token under the progress rule, also when the row
+    is entirely masked (confidence 0: the first token of the request is the fallback)."""
+    V = 16
+    x = torch.zeros(5, V)
+    x[1, :] = float("-inf")
+    x[3, :] = float("nan")
+    x[4, :] = float("-inf")
+    cu = [0, 1, 2, 5]
+    tok, conf, com = oracle_mod.commit(bits(x), V, 0.9, cu, 1)
+    np.testing.assert_array_equal(com, [1, 1, 1, 0, 0])   # request 2: row 2 (conf 1/16) beats the masked rows
+    np.testing.assert_array_equal(conf, [1 / 16, 0.0, 1 / 16, 0.0, 0.0])
+    _, _, com = oracle_mod.commit(bits(x[[1, 3, 4]]), V, 0.9, [0, 3], 1)
+    np.testing.assert_array_equal(com, [1, 0, 0])          # all masked: the first token is forced

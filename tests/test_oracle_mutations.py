@@ -58,7 +58,9 @@ COMMIT_MUTATIONS = [
     ("commit on confidence >= threshold", COMMIT, "conf_out[t] > threshold ? 1 : 0", "conf_out[t] >= threshold ? 1 : 0", 1),
     ("argmax keeps the last maximum", COMMIT, "if (x > mx) { mx = x; arg = v; }", "if (x >= mx) { mx = x; arg = v; }", 1),
     ("confidence without the exponential of the maximum removed", COMMIT,
-     "z += exp(bf16_to_double_c(row[v]) - mx);", "z += exp(bf16_to_double_c(row[v]) - mx) + 1e-3;", 1),
+     "if (x != -INFINITY) z += exp(x - mx);", "if (x != -INFINITY) z += exp(x - mx) + 1e-3;", 1),
+    ("NaN logits enter the sum", COMMIT, "return isnan(x) ? -INFINITY : x;", "return x;", 1),
+    ("a fully masked row reports a confidence", COMMIT, "conf_out[t] = 0.0;", "conf_out[t] = 1.0;", 1),
     ("progress rule picks the least confident token", COMMIT,
      "if (best < 0 || conf_out[t] > conf_out[best]) best = t;",
      "if (best < 0 || conf_out[t] < conf_out[best]) best = t;", 1),
