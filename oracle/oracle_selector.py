@@ -2,47 +2,45 @@
 
 TEST INFRASTRUCTURE ONLY: numpy fp64, exhaustive search, no code shared with the library.
 
-Sec. 5.2 models the step latency as three affine regimes over x = batch * chunk and says the
-coefficients come from offline profiling without giving the fitting procedure.  Reading: order
-the samples by x, try every pair of cuts that leaves three runs with at least two distinct x
-each and never separates equal x, fit each run with an ordinary least-squares line
-(numpy.linalg.lstsq), keep the pair of smallest total squared error (the first such pair); the
-regime boundary is the midpoint of the two samples a cut separates.
+Sec. 5.2 models the step latency over x = batch * chunk as one curve that passes through a
+memory-bound, a transition and a compute-bound regime, affine in each, with coefficients from
+offline profiling; it does not give the fitting procedure.  Reading: the curve is continuous
+(it is one latency curve, the regimes meet at their boundaries), the two boundaries lie at
+profiled loads strictly between the smallest and the largest one, and for a pair of boundaries
+b0 < b1 the four free parameters of
+    T(x) = alpha + beta * x + gamma0 * max(0, x - b0) + gamma1 * max(0, x - b1)
+are the ordinary least-squares solution (numpy.linalg.lstsq); the pair with the smallest
+squared error wins (the first such pair in (b0, b1) order).  The model is handed out per
+regime: T(x) = beta1[k] * x + beta0[k], k = 0 for x < b0, 1 for x < b1, else 2.
 Sec. 5.1: c* = argmax over the candidates of N_commit(c) * b / T(c * b).
 """
 import numpy as np
 
 
-def _line(x, t):
-    A = np.stack([x, np.ones_like(x)], axis=1)
+def _hinge_fit(x, t, b0, b1):
+    A = np.stack([np.ones_like(x), x, np.maximum(0.0, x - b0), np.maximum(0.0, x - b1)], axis=1)
     sol = np.linalg.lstsq(A, t, rcond=None)[0]
     r = t - A @ sol
-    return sol[0], sol[1], float(r @ r)
+    return sol, float(r @ r)
 
 
 def latency_fit(x, t):
-    """Returns dict(x_break [2], beta1 [3], beta0 [3], sse, cuts (a, b))."""
+    """Returns dict(x_break [2], beta1 [3], beta0 [3], sse)."""
     x = np.asarray(x, dtype=np.float64)
     t = np.asarray(t, dtype=np.float64)
-    order = np.argsort(x, kind="stable")
-    x, t = x[order], t[order]
-    n = len(x)
+    loads = np.unique(x)                      # distinct loads, ascending
+    inner = loads[1:-1]                       # a boundary has a profiled load on either side
     best = None
-    for a in range(1, n):
-        if x[a] == x[a - 1] or len(np.unique(x[:a])) < 2:
-            continue
-        l0 = _line(x[:a], t[:a])
-        for b in range(a + 1, n):
-            if x[b] == x[b - 1] or len(np.unique(x[a:b])) < 2 or len(np.unique(x[b:])) < 2:
-                continue
-            l1, l2 = _line(x[a:b], t[a:b]), _line(x[b:], t[b:])
-            sse = l0[2] + l1[2] + l2[2]
+    for i in range(len(inner)):
+        for j in range(i + 1, len(inner)):
+            b0, b1 = inner[i], inner[j]
+            (alpha, beta, g0, g1), sse = _hinge_fit(x, t, b0, b1)
             if best is None or sse < best["sse"]:
-                best = dict(x_break=np.array([(x[a - 1] + x[a]) / 2, (x[b - 1] + x[b]) / 2]),
-                            beta1=np.array([l0[0], l1[0], l2[0]]),
-                            beta0=np.array([l0[1], l1[1], l2[1]]), sse=sse, cuts=(a, b))
+                best = dict(x_break=np.array([b0, b1]),
+                            beta1=np.array([beta, beta + g0, beta + g0 + g1]),
+                            beta0=np.array([alpha, alpha - g0 * b0, alpha - g0 * b0 - g1 * b1]), sse=sse)
     if best is None:
-        raise ValueError("no admissible pair of cuts")
+        raise ValueError("fewer than four distinct loads")
     return best
 
 

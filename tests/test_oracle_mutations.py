@@ -120,9 +120,11 @@ REORG_MUTATIONS = [
     ("cu_q inclusive instead of exclusive", "cu_q = [0]", "cu_q = [int(chunk[0])] if chunk else [0]"),
 ]
 SELECTOR_MUTATIONS = [
-    ("boundary at the left sample instead of the midpoint", "(x[a - 1] + x[a]) / 2", "x[a - 1]"),
-    ("keeps the worst pair of cuts", "if best is None or sse < best[\"sse\"]:", "if best is None or sse > best[\"sse\"]:"),
-    ("intercept dropped", "np.stack([x, np.ones_like(x)], axis=1)", "np.stack([x, np.zeros_like(x)], axis=1)"),
+    ("second hinge at the first boundary", "np.maximum(0.0, x - b1)], axis=1)", "np.maximum(0.0, x - b0)], axis=1)"),
+    ("keeps the worst pair of boundaries", "if best is None or sse < best[\"sse\"]:", "if best is None or sse > best[\"sse\"]:"),
+    ("intercept dropped", "np.stack([np.ones_like(x), x,", "np.stack([np.zeros_like(x), x,"),
+    ("middle regime's intercept without the hinge shift", "beta0=np.array([alpha, alpha - g0 * b0,", "beta0=np.array([alpha, alpha,"),
+    ("last regime's slope without the second hinge", "beta1=np.array([beta, beta + g0, beta + g0 + g1])", "beta1=np.array([beta, beta + g0, beta + g0])"),
     ("regime chosen with <= at the first boundary only", "k = 0 if x < model[\"x_break\"][0] else (1 if x < model[\"x_break\"][1] else 2)",
      "k = 0 if x < model[\"x_break\"][1] else (1 if x < model[\"x_break\"][1] else 2)"),
     ("objective without the batch size in the latency", "latency_eval(model, float(batch) * chunk_sizes[i])", "latency_eval(model, float(chunk_sizes[i]))"),
