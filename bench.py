@@ -35,6 +35,8 @@ def parse_workload(name: str):
         return 1, int(name.split("_c")[1]) if "_c" in name else 32
     if name == "gqa_cb64":
         return 2, None
+    if name.startswith("gqa_cb64_c"):      # uniform-chunk diagnostic variant of configs[2]
+        return 2, int(name.split("_c")[-1])
     if name == "highload_b256":
         return 3, None
     if name.startswith("longctx_b4"):
@@ -208,7 +210,7 @@ def measure_commit(device: str, steps: int = 20):
     import torch
 
     import oracle
-    from paper_2605_24832_amd import commit_forward, commit_params, commit_workspace_bytes, inputs
+    from paper_2605_24832_amd import commit_forward, commit_params, inputs
     rng = np.random.RandomState(inputs.BASE_SEED + 3)
     rng.randint(1024, 8193, size=256)
     c = rng.choice([1, 2, 4], size=256)
@@ -217,18 +219,17 @@ def measure_commit(device: str, steps: int = 20):
     # rotate over copies so the 184 MB of logits are not served by the 256 MB memory-side cache
     xs = [inputs.make_logits(T, V, seed=inputs.BASE_SEED + 40 + k, device=device) for k in range(4)]
     p = commit_params(T, V, xs[0].shape[1], 0.9, 256, 1)
-    ws = torch.empty(commit_workspace_bytes(p) // 4 + 4, dtype=torch.float32, device=device)
     cu = torch.as_tensor(cu_h, device=device)
     tok = torch.empty(T, dtype=torch.int32, device=device)
     conf = torch.empty(T, dtype=torch.float32, device=device)
     com = torch.empty(T, dtype=torch.int32, device=device)
     for k in range(4):
-        commit_forward(p, xs[k], cu, tok, conf, com, ws)
+        commit_forward(p, xs[k], cu, tok, conf, com)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for k in range(steps):
-        commit_forward(p, xs[k % 4], cu, tok, conf, com, ws)
+        commit_forward(p, xs[k % 4], cu, tok, conf, com)
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps

@@ -28,8 +28,15 @@
  *     Logical slot n of request i lives in page block_table[i][n / P], in-page
  *     slot n % P.  Slots at or beyond L_i + c_i and unreferenced pages are
  *     never read into a result, whatever they hold (NaN included).
+ *   - How K/V get into that layout: only through this library.  The K/V of
+ *     a prompt or of any other already computed tokens (prefix caching, Sec.
+ *     4.2) are written with optimus_kv_write from plain [n, Hkv, D] rows;
+ *     the K/V of the chunk of a decoding iteration with optimus_kv_append.
+ *     Both take the same rows and produce the same bytes for the same slots.
  *   - Every call returns an optimus_status_t (0 = OK, negative = error) and
  *     never throws.  Kernel launches are asynchronous on the given stream.
+ *     Device calls run on the device they are given (the plan's) and put the
+ *     calling thread's current device back before they return.
  */
 #ifndef OPTIMUS_ATTN_H_
 #define OPTIMUS_ATTN_H_
@@ -131,6 +138,23 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool,
                       const void* k_new, const void* v_new,
                       const int32_t* block_table, void* hip_stream);
 
+/* Sec. 4.2 (cached prefix) / Sec. 6 (K/V states mapped into the paged cache), without a
+ * plan: tokens 0..n-1 of k_src / v_src (bf16 [n, Hkv, D], device memory, 16-byte aligned)
+ * are written to the logical slots first_slot .. first_slot+n-1 of request `req`, i.e. to
+ * page block_table[req][slot / P], in the pool layout described at the top; whatever the
+ * slots held is overwritten.  This is how a prompt's K/V (prefill) or recomputed K/V of
+ * committed tokens reach the pool; there is no limit on n other than the block-table row.
+ * `params` gives the geometry (same validation as optimus_attn_plan_create; mask_mode,
+ * out_dtype and softmax_scale are not used).  block_table is device memory
+ * [*, max_pages_per_req]; entries outside [0, num_pages) make the kernel skip that page's
+ * tokens.  Nothing is allocated; asynchronous on the stream; the caller's current device
+ * is left unchanged.  Errors: OPTIMUS_ERR_INVALID_ARGUMENT (null / misaligned pointers,
+ * negative req / first_slot / n), OPTIMUS_ERR_UNSUPPORTED_SHAPE,
+ * OPTIMUS_ERR_BLOCK_TABLE_TOO_SHORT (ceil((first_slot+n)/P) > max_pages_per_req).         */
+int optimus_kv_write(const optimus_attn_params_t* params, int device, void* k_pool, void* v_pool,
+                     const void* k_src, const void* v_src, const int32_t* block_table,
+                     int32_t req, int32_t first_slot, int32_t n, void* hip_stream);
+
 /* Sec. 6: attention of every chunk over its cached prefix and itself.  The
  * chunk's K/V must already be in the pool (optimus_kv_append on the same
  * stream).  out: [T, Hq, D] in params.out_dtype.  workspace: device scratch
@@ -170,13 +194,16 @@ int optimus_attn_timing_read(optimus_attn_plan_t* plan, float* total_ms_out,
  * Commit step (Sec. 2.3, Sec. 4.1; threshold 0.9 in Sec. 7.1): every chunk
  * position gets a confidence and the positions whose confidence exceeds the
  * threshold are committed.  Reading: confidence = largest softmax probability
- * of the position's logit row, token = first index attaining it.  With
- * min_commit = 1 a request that has chunk tokens but none above the threshold
- * commits its most confident one (first on ties), so decoding always advances.
- * All pointers are device memory; nothing is allocated; asynchronous on the
- * stream.                                                                      */
+ * of the position's logit row, token = first index attaining it.  A logit
+ * that is -inf or NaN is an entry that cannot be chosen and adds nothing to
+ * the softmax; a row without any other entry gets token 0, confidence 0.
+ * With min_commit = 1 a request that has chunk tokens but none above the
+ * threshold commits its most confident one (first on ties), so decoding
+ * always advances.
+ * All pointers are device memory; nothing is allocated and no scratch is
+ * needed; asynchronous on the stream.                                          */
 typedef struct {
-  int32_t num_tokens;   /* T = rows of logits, <= 65535                          */
+  int32_t num_tokens;   /* T = rows of logits, <= 2^24                           */
   int32_t vocab;        /* V >= 1 used entries per row                           */
   int64_t row_stride;   /* elements between rows: multiple of 8, >= V rounded up
                            to a multiple of 8 (rows are read in 16-byte pieces)  */
@@ -186,15 +213,13 @@ typedef struct {
   int32_t reserved0;
 } optimus_commit_params_t;
 
-/* Scratch bytes optimus_commit_forward needs for these parameters (0 on bad ones). */
-size_t optimus_commit_workspace_bytes(const optimus_commit_params_t* params);
-
-/* logits: bf16 [T, row_stride].  cu_q: int32 [batch+1] (ignored if batch == 0).
- * token_out int32 [T], conf_out fp32 [T], commit_out int32 [T] (0/1).          */
+/* logits: bf16 [T, row_stride], 16-byte aligned.  cu_q: int32 [batch+1] (ignored if
+ * batch == 0).  token_out int32 [T], conf_out fp32 [T], commit_out int32 [T] (0/1).
+ * Returns OPTIMUS_ERR_INVALID_ARGUMENT for parameters outside the ranges above or
+ * null / misaligned pointers.                                                   */
 int optimus_commit_forward(const optimus_commit_params_t* params, int device, const void* logits,
                            const int32_t* cu_q, int32_t* token_out, float* conf_out,
-                           int32_t* commit_out, void* workspace, size_t workspace_bytes,
-                           void* hip_stream);
+                           int32_t* commit_out, void* hip_stream);
 
 /* ---------------------------------------------------------------------------
  * Step-wise reorganisation (Sec. 4.4): rebuild every request's chunk for this
@@ -220,9 +245,10 @@ int optimus_reorg_forward(int device, int32_t batch, int32_t block_size, const u
 /* ---------------------------------------------------------------------------
  * Saturation-aware chunk-size selection (Sec. 5).  Host memory only, no GPU.
  *
- * Latency model (Sec. 5.2): three affine regimes over the step's token count
- * x = batch * chunk: memory-bound, transition, compute-bound.
- *   T(x) = beta1[k] * x + beta0[k],  k = 0 if x < x_break[0], 1 if x < x_break[1], else 2. */
+ * Latency model (Sec. 5.2): one continuous curve over the step's token count
+ * x = batch * chunk with three affine regimes: memory-bound, transition, compute-bound.
+ *   T(x) = beta1[k] * x + beta0[k],  k = 0 if x < x_break[0], 1 if x < x_break[1], else 2,
+ * and neighbouring regimes take the same value at the boundary between them.               */
 typedef struct optimus_latency_model {
   double x_break[2];
   double beta1[3];
@@ -230,13 +256,14 @@ typedef struct optimus_latency_model {
 } optimus_latency_model_t;
 
 /* Fit the model to profiled samples (x_i, latency_i), 6 <= num_samples <= 2048, in any order.
- * Reading (the paper says only that the coefficients come from offline profiling): samples are
- * ordered by x, cut into three runs, each run gets its own least-squares line, and the two cuts
- * are the pair that minimises the total squared error (first such pair in (cut0, cut1) order);
- * a cut never separates equal x and every run needs two distinct x.  x_break is the midpoint
- * of the two samples a cut separates.  sse_out (may be NULL) receives the total squared error.
+ * Reading (the paper says only that the coefficients come from offline profiling): the curve is
+ *   T(x) = alpha + beta x + gamma0 max(0, x - b0) + gamma1 max(0, x - b1),
+ * the boundaries b0 < b1 are profiled loads strictly between the smallest and the largest one,
+ * for a pair of boundaries the four parameters are the least-squares solution, and the pair
+ * with the smallest squared error is kept (the first such pair in (b0, b1) order).  sse_out
+ * (may be NULL) receives the squared error of the returned model.
  * Returns OPTIMUS_ERR_INVALID_ARGUMENT for null pointers, non-finite or negative samples, or
- * when no admissible pair of cuts exists.                                                   */
+ * fewer than four distinct loads.                                                          */
 int optimus_latency_fit(int32_t num_samples, const double* x, const double* latency,
                         optimus_latency_model_t* model_out, double* sse_out);
 /* T(x) of the model (NaN for a null model). */

@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     load_library,
     status_string,
     commit_params,
-    commit_workspace_bytes,
+    kv_write,
     commit_forward,
     reorg_forward,
     LatencyModel,

@@ -14,8 +14,7 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# OPTIMUS_ATTN_LIB points at another build of the same library (A/B measurements)
-_LIB_PATH = os.environ.get("OPTIMUS_ATTN_LIB") or os.path.join(_HERE, "liboptimus_attn.so")
+_LIB_PATH = os.path.join(_HERE, "liboptimus_attn.so")
 _lib = None
 
 EXPORTS = (
@@ -24,7 +23,7 @@ EXPORTS = (
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
     "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
     "optimus_status_string", "optimus_last_hip_error",
-    "optimus_commit_workspace_bytes", "optimus_commit_forward", "optimus_reorg_forward",
+    "optimus_kv_write", "optimus_commit_forward", "optimus_reorg_forward",
     "optimus_latency_fit", "optimus_latency_eval", "optimus_select_chunk",
 )
 
@@ -103,10 +102,10 @@ def load_library():
         lib.optimus_attn_set_timing.argtypes = [vp, i32]
         lib.optimus_attn_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float),
                                                  ctypes.POINTER(ctypes.c_int32)]
-        lib.optimus_commit_workspace_bytes.argtypes = [ctypes.POINTER(_CCommitParams)]
-        lib.optimus_commit_workspace_bytes.restype = ctypes.c_size_t
+        lib.optimus_kv_write.argtypes = [ctypes.POINTER(_CParams), ctypes.c_int, vp, vp, vp, vp, vp,
+                                         i32, i32, i32, vp]
         lib.optimus_commit_forward.argtypes = [ctypes.POINTER(_CCommitParams), ctypes.c_int, vp, vp,
-                                               vp, vp, vp, vp, ctypes.c_size_t, vp]
+                                               vp, vp, vp, vp]
         lib.optimus_reorg_forward.argtypes = [ctypes.c_int, i32, i32] + [vp] * 10
         dp = ctypes.POINTER(ctypes.c_double)
         mp = ctypes.POINTER(LatencyModel)
@@ -297,19 +296,26 @@ def commit_params(num_tokens, vocab, row_stride, threshold=0.9, batch=0, min_com
     return c
 
 
-def commit_workspace_bytes(params: _CCommitParams) -> int:
-    return int(load_library().optimus_commit_workspace_bytes(ctypes.byref(params)))
-
-
-def commit_forward(params: _CCommitParams, logits, cu_q, token_out, conf_out, commit_out, workspace,
+def commit_forward(params: _CCommitParams, logits, cu_q, token_out, conf_out, commit_out,
                    device: int = 0, stream=None) -> None:
     """optimus_commit_forward on torch device tensors (argument marshalling only)."""
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = load_library().optimus_commit_forward(
         ctypes.byref(params), int(device), _ptr(logits), _ptr(cu_q), _ptr(token_out), _ptr(conf_out),
-        _ptr(commit_out), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
+        _ptr(commit_out), _stream_ptr(stream))
     if rc != 0:
         raise OptimusError(rc, "optimus_commit_forward")
+
+
+def kv_write(params: AttnParams, k_pool, v_pool, k_src, v_src, block_table, req: int, first_slot: int,
+             device: int = 0, stream=None) -> None:
+    """optimus_kv_write: the rows of ``k_src`` / ``v_src`` (bf16 ``[n, Hkv, D]``) go to the logical
+    slots ``first_slot ..`` of request ``req`` (argument marshalling only)."""
+    cp = params.to_c()
+    rc = load_library().optimus_kv_write(
+        ctypes.byref(cp), int(device), _ptr(k_pool), _ptr(v_pool), _ptr(k_src), _ptr(v_src),
+        _ptr(block_table), int(req), int(first_slot), int(k_src.shape[0]), _stream_ptr(stream))
+    if rc != 0:
+        raise OptimusError(rc, "optimus_kv_write")
 
 
 def reorg_forward(decoded, block_start, chunk_req, chunk_out, cu_q_out, prefix_len_out, q_pos_out,

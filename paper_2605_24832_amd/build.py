@@ -16,20 +16,24 @@ def sources() -> list[str]:
                   glob.glob(os.path.join(HERE, "csrc", "*.cpp")))
 
 
-def build(verbose: bool = False, out: str | None = None, defines: tuple = ()) -> str:
-    """Always recompiles.  Returns the path of the shared library (``out`` or the in-tree one)."""
+def build(verbose: bool = False) -> str:
+    """Always recompiles.  Returns the path of the in-tree shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           # no NaN reaches an fp op by construction (masked scores are replaced by a select,
-           # masked V bits are cleared): lets max() drop its signalling-NaN quieting moves
+           # Lets max() drop its signalling-NaN quieting moves.  What the kernels rely on: a
+           # key outside the item's range may hold NaN and does enter the score MFMA, but its
+           # score is replaced by -inf with an integer-compared select before any max / exp
+           # sees it, and its V bits are cleared before the second MFMA; (-inf) - (-inf) in
+           # the lazy running-max test may be NaN, and either outcome of that compare keeps
+           # -inf.  NaN in a visible input gives an undefined output, as in any attention kernel.
            "-fno-honor-nans",
            "-Wall", "-Wno-unused-function",
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
     if verbose:
         cmd += ["-Rpass-analysis=kernel-resource-usage"]
-    lib = out or LIB
-    cmd += [f"-D{d}" for d in defines] + sources() + ["-o", lib]
+    lib = LIB
+    cmd += sources() + ["-o", lib]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)

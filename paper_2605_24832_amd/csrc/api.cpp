@@ -18,6 +18,22 @@ void set_hip_error(int hip_err, const char* where) {
   g_hip_error = std::string(where) + ": " + hipGetErrorString((hipError_t)hip_err);
 }
 
+DeviceGuard::DeviceGuard(int device) {
+  hipError_t e = hipGetDevice(&prev_);
+  if (e == hipSuccess && prev_ != device) {
+    e = hipSetDevice(device);
+    switched_ = e == hipSuccess;
+  }
+  if (e != hipSuccess) {
+    set_hip_error((int)e, "hipSetDevice");
+    status_ = OPTIMUS_ERR_HIP;
+  }
+}
+
+DeviceGuard::~DeviceGuard() {
+  if (switched_) (void)hipSetDevice(prev_);
+}
+
 #define OPT_HIP(call, where)                          \
   do {                                                \
     hipError_t e_ = (call);                           \
@@ -64,11 +80,12 @@ struct optimus_attn_plan {
   size_t events_used = 0;
 };
 
-static int use_device(const optimus_attn_plan* plan) {
-  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
-  OPT_HIP(hipSetDevice(plan->device), "hipSetDevice");
-  return OPTIMUS_OK;
-}
+// Every device entry point works on the plan's device and leaves the caller's current device
+// as it found it.
+#define OPT_ON_PLAN_DEVICE(plan)                                   \
+  if ((plan)->device < 0) return OPTIMUS_ERR_NO_DEVICE;            \
+  DeviceGuard device_guard_((plan)->device);                       \
+  if (device_guard_.status() != OPTIMUS_OK) return device_guard_.status()
 
 extern "C" {
 
@@ -83,9 +100,8 @@ int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
   plan->params = *params;
   plan->device = device;
   if (device >= 0) {
-    hipError_t e = hipSetDevice(device);
     hipDeviceProp_t prop;
-    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    const hipError_t e = hipGetDeviceProperties(&prop, device);
     if (e != hipSuccess) {
       set_hip_error((int)e, "plan_create");
       optimus_attn_plan_destroy(plan);  // releases whatever was created
@@ -122,8 +138,7 @@ int optimus_attn_plan_update(optimus_attn_plan_t* plan, int32_t batch, const int
     plan->planned = true;
     return OPTIMUS_OK;
   }
-  rc = use_device(plan);
-  if (rc != OPTIMUS_OK) return rc;
+  OPT_ON_PLAN_DEVICE(plan);
 
   const HostPlan& hp = plan->host;
   static_assert(sizeof(optimus_work_item_t) == 32 && sizeof(MergeItem) == 32, "8 x int32 records");
@@ -199,8 +214,7 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
   if (!k_pool || !v_pool || !k_new || !v_new || !block_table) return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)k_new | (uintptr_t)v_new) & 15)
     return OPTIMUS_ERR_INVALID_ARGUMENT;
-  int rc = use_device(plan);
-  if (rc != OPTIMUS_OK) return rc;
+  OPT_ON_PLAN_DEVICE(plan);
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   const int n_runs = (int32_t)(plan->host.append_runs.size() / 4);
   if (!plan->dirty) {
@@ -211,7 +225,7 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
   // a work-list upload is pending: it rides in the same launch, and the runs are read from the
   // pinned copy
   const int sl = plan->slot;
-  rc = launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
+  const int rc = launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
                         (const uint16_t*)v_new, block_table, plan->staging[sl] + plan->off_runs, n_runs,
                         plan->dev_buf, plan->staging[sl], plan->upload_i32, hip_stream);
   if (rc != OPTIMUS_OK) return rc;
@@ -219,6 +233,25 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
   plan->staging_busy[sl] = true;
   plan->dirty = false;
   return OPTIMUS_OK;
+}
+
+int optimus_kv_write(const optimus_attn_params_t* params, int device, void* k_pool, void* v_pool,
+                     const void* k_src, const void* v_src, const int32_t* block_table, int32_t req,
+                     int32_t first_slot, int32_t n, void* hip_stream) {
+  if (!params || device < 0 || req < 0 || first_slot < 0 || n < 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  const int rc = validate_params(*params);
+  if (rc != OPTIMUS_OK) return rc;
+  if ((int64_t)first_slot + n > (int64_t)INT32_MAX - kTileTokens) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (n == 0) return OPTIMUS_OK;
+  if (((int64_t)first_slot + n + params->page_size - 1) / params->page_size > params->max_pages_per_req)
+    return OPTIMUS_ERR_BLOCK_TABLE_TOO_SHORT;
+  if (!k_pool || !v_pool || !k_src || !v_src || !block_table) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)k_src | (uintptr_t)v_src) & 15)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  DeviceGuard guard(device);
+  if (guard.status() != OPTIMUS_OK) return guard.status();
+  return launch_kv_write(*params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_src,
+                         (const uint16_t*)v_src, block_table, req, first_slot, n, hip_stream);
 }
 
 int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
@@ -234,11 +267,10 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
     return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (hp.workspace_bytes > 0 && (!workspace || workspace_bytes < hp.workspace_bytes))
     return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
-  int rc = use_device(plan);
-  if (rc != OPTIMUS_OK) return rc;
+  OPT_ON_PLAN_DEVICE(plan);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  rc = flush_upload(plan, s);
+  int rc = flush_upload(plan, s);
   if (rc != OPTIMUS_OK) return rc;
   const optimus_attn_params_t& p = plan->params;
   const int32_t* d = plan->dev_buf;
@@ -286,15 +318,18 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
 
 void optimus_attn_plan_destroy(optimus_attn_plan_t* plan) {
   if (!plan) return;
-  if (plan->device >= 0 && hipSetDevice(plan->device) == hipSuccess) {
-    (void)hipDeviceSynchronize();  // nothing of ours may still read the buffers
-    if (plan->dev_buf) (void)hipFree(plan->dev_buf);
-    for (int32_t* b : plan->retired) (void)hipFree(b);
-    for (int r = 0; r < optimus_attn_plan::kRing; ++r) {
-      if (plan->staging[r]) (void)hipHostFree(plan->staging[r]);
-      if (plan->staging_done[r]) (void)hipEventDestroy(plan->staging_done[r]);
+  if (plan->device >= 0) {
+    DeviceGuard guard(plan->device);
+    if (guard.status() == OPTIMUS_OK) {
+      (void)hipDeviceSynchronize();  // nothing of ours may still read the buffers
+      if (plan->dev_buf) (void)hipFree(plan->dev_buf);
+      for (int32_t* b : plan->retired) (void)hipFree(b);
+      for (int r = 0; r < optimus_attn_plan::kRing; ++r) {
+        if (plan->staging[r]) (void)hipHostFree(plan->staging[r]);
+        if (plan->staging_done[r]) (void)hipEventDestroy(plan->staging_done[r]);
+      }
+      for (hipEvent_t e : plan->events) (void)hipEventDestroy(e);
     }
-    for (hipEvent_t e : plan->events) (void)hipEventDestroy(e);
   }
   delete plan;
 }
@@ -325,9 +360,7 @@ int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable) {
 
 int optimus_attn_timing_read(optimus_attn_plan_t* plan, float* total_ms_out, int32_t* forwards_out) {
   if (!plan || !total_ms_out || !forwards_out) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
-  int rc = use_device(plan);
-  if (rc != OPTIMUS_OK) return rc;
+  OPT_ON_PLAN_DEVICE(plan);
   float total = 0.f;
   for (size_t i = 0; i + 1 < plan->events_used; i += 2) {
     float ms = 0.f;

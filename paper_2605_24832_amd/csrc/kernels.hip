@@ -485,13 +485,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
   constexpr int KS = D / 32, DB = D / 16, P = 1 << LGP;
   constexpr int PIECES = D * 4;        // 16-byte pieces of a K (= of a V) tile
   constexpr int LPT = PIECES / 256;    // pieces per thread per tensor per tile
-#ifndef OPT_PF_NT1
-#define OPT_PF_NT1 2
-#endif
-#ifndef OPT_PF_NT2
-#define OPT_PF_NT2 2
-#endif
-  constexpr int PF = NT == 1 ? OPT_PF_NT1 : OPT_PF_NT2;  // register sets of prefetched tiles
+  constexpr int PF = 2;                // register sets of prefetched tiles
   u32x4 (*sm_k)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem);
   u32x4 (*sm_v)[PIECES] = reinterpret_cast<u32x4 (*)[PIECES]>(smem + 2 * PIECES * 4);
 
@@ -862,9 +856,10 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
   // piece e = (4*i + wave)*64 + lane of the layouts above.
   // 16-key pages: a tile is two pages, and each page's K block ([d group][key][8]) and V block
   // ([d][16 keys]) goes to LDS as it lies in memory, page after page, so that every load
-  // instruction reads one page (uniform base in scalar registers, lane i takes bytes 16i..):
-  //   K piece a*PIECES/2 + g8*16 + key%16,  V piece a*PIECES/2 + 2*d + half  (a = key/16).
-  // Eight consecutive lanes still read eight different 16-byte bank groups in both products.
+  // instruction reads 1 KB of one page (uniform base in scalar registers):
+  //   K piece a*PIECES/2 + g8*16 + key%16,  V piece a*PIECES/2 + 2*d + (half ^ ((d>>3)&1))
+  // (a = key/16).  The 16 lanes an LDS cycle serves (16 consecutive rows of S^T or of V^T)
+  // read 16 different 16-byte bank groups in both products.
   uint32_t ksrc[LPT], vsrc[LPT];
   if constexpr (LGP != 4) {
 #pragma unroll
@@ -878,6 +873,11 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     }
   }
   const uint32_t lane16 = (uint32_t)lane * 16u;
+  // V of a 16-key page: the two 16-byte halves of the rows d with bit 3 set are fetched
+  // swapped, i.e. LDS piece 2*d + (half ^ ((d >> 3) & 1)) holds (d, half).  Sixteen
+  // consecutive rows of one half, which is what 16 consecutive lanes read as an operand, then
+  // lie in sixteen different 16-byte bank groups (unswizzled they would share eight).
+  const uint32_t lane16_v = (uint32_t)(lane ^ ((lane >> 4) & 1)) * 16u;
   constexpr int IPP = D / 32;   // load instructions (1 KB each) per 16-key page and tensor
   // this lane's K operand piece within a stage (score product st adds 32*st resp. 64*st) and
   // its V operand piece for d = r32, key half 0 (see SOFTMAX_PV)
@@ -921,7 +921,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 #pragma unroll
       for (int i = 0; i < LPT; ++i) {
         const int j = 4 * i + wave;
-        load_to_lds_16<STREAM>((j / IPP ? v1 : v0) + (j % IPP) * 1024, lane16, dst + 16u * (PIECES + 256 * i));
+        load_to_lds_16<STREAM>((j / IPP ? v1 : v0) + (j % IPP) * 1024, lane16_v, dst + 16u * (PIECES + 256 * i));
       }
     } else {
 #pragma unroll
@@ -977,7 +977,7 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 #pragma unroll
       for (int aa = 0; aa < 2; ++aa) {
         const int d = 32 * db + r32, o = 2 * aa + h;
-        u32x4 vv = LGP == 4 ? vb[aa * (PIECES / 2) + 2 * d + h] : vb[4 * d + (o ^ ((d >> 2) & 3))];
+        u32x4 vv = LGP == 4 ? vb[aa * (PIECES / 2) + 2 * d + (h ^ ((d >> 3) & 1))] : vb[4 * d + (o ^ ((d >> 2) & 3))];
         if (masked) {   // keys at or beyond kv_end may hold anything: zero them
           const int cnt = it.kv_end - (key0 + 16 * aa);
           vv.x &= keep_mask(cnt); vv.y &= keep_mask(cnt - 2);
@@ -1113,8 +1113,8 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
 //
 template <int D, int LGP>
 __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
-  constexpr int kFloats0 = split_wave_smem_floats<D, 2>() > lds_tile_smem_floats<D>()
-                               ? split_wave_smem_floats<D, 2>() : lds_tile_smem_floats<D>();
+  constexpr int kFloats0 = split_wave_smem_floats<D, 1>() > lds_tile_smem_floats<D>()
+                               ? split_wave_smem_floats<D, 1>() : lds_tile_smem_floats<D>();
   constexpr int kFloats = kFloats0 > wide_smem_floats<D>() ? kFloats0 : wide_smem_floats<D>();
   __shared__ __attribute__((aligned(16))) float smem[kFloats];
   const optimus_work_item_t it = a.items[blockIdx.x];
@@ -1129,9 +1129,6 @@ __global__ __launch_bounds__(W * 64, 2) void attn_kernel(KernelArgs a) {
     else wide_tile_body<D, LGP, false>(a, it, smem);
   }
   else if (it.row_count <= 16) split_wave_body<D, LGP, 1>(a, it, smem);
-#ifdef OPT_SPLIT2
-  else if (it.row_count <= 32) split_wave_body<D, LGP, 2>(a, it, smem);
-#endif
   else lds_tile_body<D, LGP, 1>(a, it, smem);
 }
 
@@ -1230,43 +1227,41 @@ __global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
 // memory write, which made the token-by-token version write 9x its payload.
 struct AppendRun { int32_t req, token0, slot0, count; };
 
+struct PoolGeometry {
+  int32_t num_kv_heads, page_size, lgp, max_pages_per_req, num_pages;
+  int64_t k_stride_page, k_stride_head, v_stride_page, v_stride_head;
+};
+
+// Writes the `r.count` (1..8) tokens src[r.token0 ..] to the logical slots r.slot0.. of request
+// r.req; all of them lie in one aligned group of 8 slots.  A block-table entry outside the
+// pool writes nothing.
 template <int D>
-__global__ __launch_bounds__(256) void kv_append_kernel(
-    uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const uint16_t* __restrict__ k_new,
-    const uint16_t* __restrict__ v_new, const int32_t* __restrict__ block_table,
-    const AppendRun* __restrict__ runs, int num_kv_heads, int page_size, int lgp,
-    int max_pages_per_req, int64_t k_stride_page, int64_t k_stride_head, int64_t v_stride_page,
-    int64_t v_stride_head, u32x4* __restrict__ upload_dst, const u32x4* __restrict__ upload_src,
-    size_t upload_n, int upload_blocks) {
-  // The first upload_blocks workgroups carry a pending work-list upload (pinned host memory ->
-  // device) so that it does not cost a launch of its own; `runs` then points into the pinned
-  // copy, which is complete before the launch, not into the device copy being written.
-  if ((int)blockIdx.x < upload_blocks) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < upload_n) upload_dst[i] = upload_src[i];
-    return;
-  }
-  const AppendRun r = runs[blockIdx.x - upload_blocks];
-  const int64_t page = block_table[(int64_t)r.req * max_pages_per_req + (r.slot0 >> lgp)];
+__device__ __forceinline__ void write_run(uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool,
+                                          const uint16_t* __restrict__ k_src, const uint16_t* __restrict__ v_src,
+                                          const int32_t* __restrict__ block_table, const AppendRun r,
+                                          const PoolGeometry& g) {
+  const int64_t page = block_table[(int64_t)r.req * g.max_pages_per_req + (r.slot0 >> g.lgp)];
+  if ((uint64_t)page >= (uint64_t)g.num_pages) return;   // uniform per block
+  const int page_size = g.page_size;
   const int slot = r.slot0 & (page_size - 1);
-  const int64_t row = (int64_t)num_kv_heads * D;       // elements per token of k_new / v_new
-  const uint16_t* ksrc = k_new + (int64_t)r.token0 * row;
-  const uint16_t* vsrc = v_new + (int64_t)r.token0 * row;
-  uint16_t* kp = k_pool + page * k_stride_page;
-  uint16_t* vp = v_pool + page * v_stride_page;
-  const int kpieces = num_kv_heads * (D / 8);
+  const int64_t row = (int64_t)g.num_kv_heads * D;       // elements per token of the source
+  const uint16_t* ksrc = k_src + (int64_t)r.token0 * row;
+  const uint16_t* vsrc = v_src + (int64_t)r.token0 * row;
+  uint16_t* kp = k_pool + page * g.k_stride_page;
+  uint16_t* vp = v_pool + page * g.v_stride_page;
+  const int kpieces = g.num_kv_heads * (D / 8);
   for (int e = threadIdx.x; e < r.count * kpieces; e += 256) {
     const int j = e / kpieces, rem = e - j * kpieces;
-    const int g = rem / (D / 8), dg = rem % (D / 8);
-    const u32x4 x = *reinterpret_cast<const u32x4*>(ksrc + j * row + g * D + dg * 8);
-    *reinterpret_cast<u32x4*>(kp + (int64_t)g * k_stride_head + ((int64_t)dg * page_size + slot + j) * 8) = x;
+    const int h = rem / (D / 8), dg = rem % (D / 8);
+    const u32x4 x = *reinterpret_cast<const u32x4*>(ksrc + j * row + h * D + dg * 8);
+    *reinterpret_cast<u32x4*>(kp + (int64_t)h * g.k_stride_head + ((int64_t)dg * page_size + slot + j) * 8) = x;
   }
-  for (int e = threadIdx.x; e < num_kv_heads * D; e += 256) {
-    const int g = e / D, d = e % D;
+  for (int e = threadIdx.x; e < g.num_kv_heads * D; e += 256) {
+    const int h = e / D, d = e % D;
     // w[p]: value for position p of the aligned group of 8 slots (register indices are
     // compile-time; first and count are the same for the whole block: no divergence)
     const int first = slot & 7;
-    uint16_t* dst = vp + (int64_t)g * v_stride_head + (int64_t)d * page_size + (slot - first);
+    uint16_t* dst = vp + (int64_t)h * g.v_stride_head + (int64_t)d * page_size + (slot - first);
     uint32_t w[8];
     bool on[8];
 #pragma unroll
@@ -1294,6 +1289,36 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
       }
     }
   }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_kernel(
+    uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const uint16_t* __restrict__ k_new,
+    const uint16_t* __restrict__ v_new, const int32_t* __restrict__ block_table,
+    const AppendRun* __restrict__ runs, PoolGeometry g, u32x4* __restrict__ upload_dst,
+    const u32x4* __restrict__ upload_src, size_t upload_n, int upload_blocks) {
+  // The first upload_blocks workgroups carry a pending work-list upload (pinned host memory ->
+  // device) so that it does not cost a launch of its own; `runs` then points into the pinned
+  // copy, which is complete before the launch, not into the device copy being written.
+  if ((int)blockIdx.x < upload_blocks) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < upload_n) upload_dst[i] = upload_src[i];
+    return;
+  }
+  write_run<D>(k_pool, v_pool, k_new, v_new, block_table, runs[blockIdx.x - upload_blocks], g);
+}
+
+// Plan-independent writer: tokens 0..n-1 of (k_src, v_src) go to the logical slots
+// first_slot.. of request `req`.  Block b takes the b-th aligned group of 8 slots the range touches.
+template <int D>
+__global__ __launch_bounds__(256) void kv_write_kernel(
+    uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const uint16_t* __restrict__ k_src,
+    const uint16_t* __restrict__ v_src, const int32_t* __restrict__ block_table, int req,
+    int first_slot, int n, PoolGeometry g) {
+  const int group = (first_slot >> 3) + (int)blockIdx.x;
+  const int lo = max(first_slot, group * 8), hi = min(first_slot + n, group * 8 + 8);
+  if (lo >= hi) return;
+  write_run<D>(k_pool, v_pool, k_src, v_src, block_table, AppendRun{req, lo - first_slot, lo, hi - lo}, g);
 }
 
 // ------------------------------------------------------------------ launchers
@@ -1337,6 +1362,16 @@ int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_
   return OPTIMUS_OK;
 }
 
+static PoolGeometry pool_geometry(const optimus_attn_params_t& p) {
+  PoolGeometry g{};
+  g.num_kv_heads = p.num_kv_heads; g.page_size = p.page_size; g.lgp = 0;
+  while ((1 << g.lgp) < p.page_size) ++g.lgp;
+  g.max_pages_per_req = p.max_pages_per_req; g.num_pages = p.num_pages;
+  g.k_stride_page = p.k_stride_page; g.k_stride_head = p.k_stride_head;
+  g.v_stride_page = p.v_stride_page; g.v_stride_head = p.v_stride_head;
+  return g;
+}
+
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
                      const int32_t* runs, int32_t n_runs, int32_t* upload_dst,
@@ -1348,22 +1383,36 @@ int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t*
   u32x4* ud = reinterpret_cast<u32x4*>(upload_dst);
   const u32x4* us = reinterpret_cast<const u32x4*>(upload_src);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  int lgp = 0;
-  while ((1 << lgp) < p.page_size) ++lgp;
   const dim3 grid(n_runs + up_blocks), block(256);
   const AppendRun* r = reinterpret_cast<const AppendRun*>(runs);
+  const PoolGeometry g = pool_geometry(p);
   if (p.head_dim == 128)
     hipLaunchKernelGGL((kv_append_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
-                       block_table, r, p.num_kv_heads, p.page_size, lgp,
-                       p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
-                       p.v_stride_head, ud, us, up_n, up_blocks);
+                       block_table, r, g, ud, us, up_n, up_blocks);
   else
     hipLaunchKernelGGL((kv_append_kernel<64>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
-                       block_table, r, p.num_kv_heads, p.page_size, lgp,
-                       p.max_pages_per_req, p.k_stride_page, p.k_stride_head, p.v_stride_page,
-                       p.v_stride_head, ud, us, up_n, up_blocks);
+                       block_table, r, g, ud, us, up_n, up_blocks);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error((int)e, "kv_append kernel launch"); return OPTIMUS_ERR_HIP; }
+  return OPTIMUS_OK;
+}
+
+int launch_kv_write(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
+                    const uint16_t* k_src, const uint16_t* v_src, const int32_t* block_table,
+                    int32_t req, int32_t first_slot, int32_t n, void* stream) {
+  if (n <= 0) return OPTIMUS_OK;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const int groups = ((first_slot + n - 1) >> 3) - (first_slot >> 3) + 1;
+  const dim3 grid(groups), block(256);
+  const PoolGeometry g = pool_geometry(p);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL((kv_write_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_src, v_src,
+                       block_table, req, first_slot, n, g);
+  else
+    hipLaunchKernelGGL((kv_write_kernel<64>), grid, block, 0, s, k_pool, v_pool, k_src, v_src,
+                       block_table, req, first_slot, n, g);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_hip_error((int)e, "kv_write kernel launch"); return OPTIMUS_ERR_HIP; }
   return OPTIMUS_OK;
 }
 

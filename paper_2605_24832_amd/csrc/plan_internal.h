@@ -13,30 +13,18 @@ namespace optimus {
 constexpr int kTileTokens = 32;     // keys per MFMA tile step (one 16x16x32 PV contraction)
 constexpr int kRowsPerSubtile = 16; // query rows per MFMA N tile
 constexpr int kWavesPerBlock = 4;
-// Work items by query-row count: <= 16 rows run the split-wave body (the waves split the
-// keys), 17..128 rows the lds-tile body with 1..2 subtiles per wave (the waves split the
-// rows).  A (request, kv head) pair with more rows is cut into row tiles of 128.
+// Work items by query-row count.  A (request, kv head) pair with more than kMaxRowsPerItem
+// rows is cut into row tiles of that many.  Pairs with more than kWideMinRows rows run the
+// wide body (32 rows per wave, all their row tiles, also a narrow last one); of the others,
+// items of at most 16 rows run the split-wave body (the waves split the keys) and items of
+// 17..64 rows the lds-tile body (the waves split the rows, 16 each).
 constexpr int kMaxRowsPerItem = 128;
-#ifndef OPT_WIDE_MIN_ROWS
-#define OPT_WIDE_MIN_ROWS 64
-#endif
-constexpr int kWideMinRows = OPT_WIDE_MIN_ROWS;     // (request, kv head) pairs with more query rows take the wide body
+constexpr int kWideMinRows = 64;
 constexpr int kNumXcd = 8;  // accelerator dies of an MI355X; workgroup i runs on die i % 8
 // Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
 // scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
 // In tenths, so that costs stay small integers.
-inline int tile_cost10_of_rows(int rows) {
-#ifndef OPT_COST_MID
-#define OPT_COST_MID 11
-#endif
-#ifndef OPT_COST_WIDE
-#define OPT_COST_WIDE 12
-#endif
-  if (rows <= 16) return 10;
-  if (rows <= 64) return OPT_COST_MID;
-  return OPT_COST_WIDE;
-}
-inline double tile_cost_of_rows(int rows) { return 0.1 * tile_cost10_of_rows(rows); }
+constexpr int tile_cost10_of_rows(int rows) { return rows <= 16 ? 10 : (rows <= kWideMinRows ? 11 : 12); }
 
 // One merge job: `n_splits` partials of the same q tile, stored back to back
 // (`row_count` rows each) starting at workspace row `first_part_row`.
@@ -129,10 +117,31 @@ int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t*
                      const int32_t* runs, int32_t n_runs, int32_t* upload_dst,
                      const int32_t* upload_src, size_t upload_i32, void* stream);
 
+// Tokens 0..n-1 of k_src / v_src ([n, Hkv, D]) -> logical slots first_slot.. of request `req`.
+int launch_kv_write(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
+                    const uint16_t* k_src, const uint16_t* v_src, const int32_t* block_table,
+                    int32_t req, int32_t first_slot, int32_t n, void* stream);
+
 // Copy n_i32 (a multiple of 4) int32 from pinned host memory to device memory with a kernel on
 // `stream` (shorter than the copy engine's start-up for the few tens of KB of a work list).
 int launch_upload(int32_t* dst_device, const int32_t* src_pinned_host, size_t n_i32, void* stream);
 
 void set_hip_error(int hip_err, const char* where);
+
+// Makes `device` the calling thread's current HIP device for the life of the object and puts
+// the caller's device back afterwards.  status() is OPTIMUS_OK or OPTIMUS_ERR_HIP.
+class DeviceGuard {
+ public:
+  explicit DeviceGuard(int device);
+  ~DeviceGuard();
+  DeviceGuard(const DeviceGuard&) = delete;
+  DeviceGuard& operator=(const DeviceGuard&) = delete;
+  int status() const { return status_; }
+
+ private:
+  int prev_ = -1;
+  bool switched_ = false;
+  int status_ = 0;
+};
 
 }  // namespace optimus

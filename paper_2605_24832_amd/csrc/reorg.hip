@@ -89,8 +89,8 @@ extern "C" int optimus_reorg_forward(int device, int32_t batch, int32_t block_si
   if (batch > 0 && (!decoded || !block_start || !chunk_req || !chunk_out || !prefix_len_out ||
                     !q_pos_out || !kv_slot_out || !token_req_out))
     return OPTIMUS_ERR_INVALID_ARGUMENT;
-  hipError_t e = hipSetDevice(device);
-  if (e != hipSuccess) { set_hip_error((int)e, "hipSetDevice"); return OPTIMUS_ERR_HIP; }
+  DeviceGuard guard(device);   // the caller's current device is put back on return
+  if (guard.status() != OPTIMUS_OK) return guard.status();
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(reorg_count_kernel, dim3(1), dim3(1024), 0, s, decoded, block_start, chunk_req,
                      batch, block_size, chunk_out, cu_q_out, prefix_len_out);
@@ -98,7 +98,7 @@ extern "C" int optimus_reorg_forward(int device, int32_t batch, int32_t block_si
     hipLaunchKernelGGL(reorg_emit_kernel, dim3((batch + 3) / 4), dim3(256), 0, s, decoded,
                        block_start, chunk_out, cu_q_out, prefix_len_out, batch, block_size,
                        q_pos_out, kv_slot_out, token_req_out);
-  e = hipGetLastError();
+  const hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_hip_error((int)e, "reorg kernel launch"); return OPTIMUS_ERR_HIP; }
   return OPTIMUS_OK;
 }

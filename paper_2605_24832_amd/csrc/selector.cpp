@@ -1,8 +1,15 @@
 // Saturation-aware chunk-size selection (Optimus Sec. 5): a three-regime
 // piecewise-affine latency model over x = batch * chunk (Sec. 5.2), fitted to
-// profiled samples by least squares with the two regime boundaries chosen to
-// minimise the total squared error, and the per-step choice
+// profiled samples as ONE continuous curve by least squares with the two regime
+// boundaries searched over the profiled loads, and the per-step choice
 // c* = argmax_c N_commit(c) * b / T(c * b) (Sec. 5.1).  Host code only.
+//
+// Fit.  T(x) = alpha + beta x + gamma0 max(0, x - b0) + gamma1 max(0, x - b1).  For a pair
+// of boundaries the normal equations of the four parameters need only sums of 1, x, x^2, t,
+// x t over the samples above a boundary, so with suffix sums over the sorted samples every
+// pair costs O(1); all pairs of interior distinct loads are tried.  Loads are scaled to
+// [0, 1] and latencies centred, sums and the 4 x 4 solves are in long double, and the
+// reported squared error is recomputed from the residuals of the chosen model.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -15,25 +22,7 @@
 
 namespace {
 
-// Running least-squares sums of one segment, updated one sample at a time
-// (Welford's recurrences: no cancellation between large sums).
-struct Segment {
-  double n = 0, mx = 0, mt = 0, sxx = 0, sxt = 0, stt = 0;
-  void add(double x, double t) {
-    n += 1;
-    const double dx = x - mx, dt = t - mt;
-    mx += dx / n;
-    mt += dt / n;
-    sxx += dx * (x - mx);
-    sxt += dx * (t - mt);
-    stt += dt * (t - mt);
-  }
-  bool has_slope() const { return sxx > 0; }
-  double slope() const { return sxt / sxx; }
-  double intercept() const { return mt - slope() * mx; }
-  double sse() const { return std::max(0.0, stt - sxt * sxt / sxx); }
-};
-
+typedef long double ld;
 constexpr int kMaxSamples = 2048;
 
 // Finite test on the bit pattern: the library is built with NaN-free floating-point
@@ -43,6 +32,34 @@ bool finite_bits(double v) {
   std::memcpy(&u, &v, sizeof u);
   return ((u >> 52) & 0x7ff) != 0x7ff;
 }
+
+// Solves the symmetric 4 x 4 system m p = r by Gaussian elimination with partial pivoting.
+// Returns false if a pivot vanishes (cannot happen for boundaries strictly between the
+// smallest and the largest load).
+bool solve4(ld m[4][4], ld r[4], ld p[4]) {
+  int perm[4] = {0, 1, 2, 3};
+  for (int c = 0; c < 4; ++c) {
+    int piv = c;
+    for (int k = c + 1; k < 4; ++k)
+      if (std::fabs(m[perm[k]][c]) > std::fabs(m[perm[piv]][c])) piv = k;
+    std::swap(perm[c], perm[piv]);
+    const ld d = m[perm[c]][c];
+    if (d == 0) return false;
+    for (int k = c + 1; k < 4; ++k) {
+      const ld f = m[perm[k]][c] / d;
+      for (int j = c; j < 4; ++j) m[perm[k]][j] -= f * m[perm[c]][j];
+      r[perm[k]] -= f * r[perm[c]];
+    }
+  }
+  for (int c = 3; c >= 0; --c) {
+    ld v = r[perm[c]];
+    for (int j = c + 1; j < 4; ++j) v -= m[perm[c]][j] * p[j];
+    p[c] = v / m[perm[c]][c];
+  }
+  return true;
+}
+
+struct Sums { ld n, x, xx, t, xt; };
 
 }  // namespace
 
@@ -56,44 +73,78 @@ extern "C" int optimus_latency_fit(int32_t num_samples, const double* x, const d
   std::vector<int> order(n);
   std::iota(order.begin(), order.end(), 0);
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return x[a] < x[b]; });
-  std::vector<double> xs(n), ts(n);
-  for (int i = 0; i < n; ++i) { xs[i] = x[order[i]]; ts[i] = latency[order[i]]; }
+  const double x_max = x[order[n - 1]];
+  if (!(x_max > 0)) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  ld t_mean = 0;
+  for (int i = 0; i < n; ++i) t_mean += latency[i];
+  t_mean /= n;
+  std::vector<ld> u(n), tc(n);
+  for (int i = 0; i < n; ++i) { u[i] = (ld)x[order[i]] / x_max; tc[i] = latency[order[i]] - t_mean; }
 
-  // cost[i * (n + 1) + j] = squared error of the best line through samples [i, j); inf where the
-  // segment has fewer than two distinct x
-  const double inf = std::numeric_limits<double>::infinity();
-  std::vector<double> cost((size_t)(n + 1) * (n + 1), inf);
-  for (int i = 0; i < n; ++i) {
-    Segment s;
-    for (int j = i; j < n; ++j) {
-      s.add(xs[j], ts[j]);
-      if (s.has_slope()) cost[(size_t)i * (n + 1) + j + 1] = s.sse();
+  // suf[i]: sums over the sorted samples i .. n-1
+  std::vector<Sums> suf(n + 1, Sums{0, 0, 0, 0, 0});
+  ld tt = 0;
+  for (int i = n - 1; i >= 0; --i) {
+    suf[i] = Sums{suf[i + 1].n + 1, suf[i + 1].x + u[i], suf[i + 1].xx + u[i] * u[i], suf[i + 1].t + tc[i],
+                  suf[i + 1].xt + u[i] * tc[i]};
+    tt += tc[i] * tc[i];
+  }
+  // distinct loads: first[g] = index of the first sample of the g-th distinct load
+  std::vector<int> first;
+  for (int i = 0; i < n; ++i)
+    if (i == 0 || x[order[i]] != x[order[i - 1]]) first.push_back(i);
+  const int d = (int)first.size();
+  if (d < 4) return OPTIMUS_ERR_INVALID_ARGUMENT;   // no room for two boundaries between the extreme loads
+  first.push_back(n);
+
+  const Sums& all = suf[0];
+  ld best = std::numeric_limits<ld>::infinity();
+  int best0 = -1, best1 = -1;
+  ld best_p[4] = {0, 0, 0, 0};
+  for (int g0 = 1; g0 + 1 < d - 1; ++g0) {
+    const ld b0 = u[first[g0]];
+    const Sums& a0 = suf[first[g0 + 1]];            // samples above b0
+    // hinge h0 = max(0, u - b0): sums of h0, h0 u, h0^2, h0 t
+    const ld h0 = a0.x - b0 * a0.n, h0x = a0.xx - b0 * a0.x, h0h0 = a0.xx - 2 * b0 * a0.x + b0 * b0 * a0.n;
+    const ld h0t = a0.xt - b0 * a0.t;
+    for (int g1 = g0 + 1; g1 < d - 1; ++g1) {
+      const ld b1 = u[first[g1]];
+      const Sums& a1 = suf[first[g1 + 1]];          // samples above b1
+      const ld h1 = a1.x - b1 * a1.n, h1x = a1.xx - b1 * a1.x, h1h1 = a1.xx - 2 * b1 * a1.x + b1 * b1 * a1.n;
+      const ld h1t = a1.xt - b1 * a1.t;
+      const ld h0h1 = a1.xx - (b0 + b1) * a1.x + b0 * b1 * a1.n;
+      ld m[4][4] = {{all.n, all.x, h0, h1}, {all.x, all.xx, h0x, h1x}, {h0, h0x, h0h0, h0h1}, {h1, h1x, h0h1, h1h1}};
+      ld r[4] = {all.t, all.xt, h0t, h1t};
+      const ld r0[4] = {all.t, all.xt, h0t, h1t};
+      ld p[4];
+      if (!solve4(m, r, p)) continue;
+      const ld sse = tt - (p[0] * r0[0] + p[1] * r0[1] + p[2] * r0[2] + p[3] * r0[3]);
+      if (sse < best) {
+        best = sse; best0 = g0; best1 = g1;
+        for (int k = 0; k < 4; ++k) best_p[k] = p[k];
+      }
     }
   }
-  // a boundary may only fall between two different x: equal loads belong to one regime
-  double best = inf;
-  int best_a = -1, best_b = -1;
-  for (int a = 1; a < n; ++a) {
-    if (xs[a] == xs[a - 1]) continue;
-    const double c0 = cost[a];
-    if (c0 == inf) continue;
-    for (int b = a + 1; b < n; ++b) {
-      if (xs[b] == xs[b - 1]) continue;
-      const double total = c0 + cost[(size_t)a * (n + 1) + b] + cost[(size_t)b * (n + 1) + n];
-      if (total < best) { best = total; best_a = a; best_b = b; }
+  if (best0 < 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  const ld b0 = u[first[best0]], b1 = u[first[best1]];
+  const ld alpha = best_p[0] + t_mean, beta = best_p[1], g0 = best_p[2], g1 = best_p[3];
+  model_out->x_break[0] = x[order[first[best0]]];
+  model_out->x_break[1] = x[order[first[best1]]];
+  model_out->beta1[0] = (double)(beta / x_max);
+  model_out->beta1[1] = (double)((beta + g0) / x_max);
+  model_out->beta1[2] = (double)((beta + g0 + g1) / x_max);
+  model_out->beta0[0] = (double)alpha;
+  model_out->beta0[1] = (double)(alpha - g0 * b0);
+  model_out->beta0[2] = (double)(alpha - g0 * b0 - g1 * b1);
+  if (sse_out) {
+    ld sse = 0;
+    for (int i = 0; i < n; ++i) {
+      const ld ui = u[i];
+      const ld fit = best_p[0] + beta * ui + g0 * std::max<ld>(0, ui - b0) + g1 * std::max<ld>(0, ui - b1);
+      sse += (tc[i] - fit) * (tc[i] - fit);
     }
+    *sse_out = (double)sse;
   }
-  if (best_a < 0) return OPTIMUS_ERR_INVALID_ARGUMENT;  // fewer than six usable distinct loads
-  const int lo[3] = {0, best_a, best_b}, hi[3] = {best_a, best_b, n};
-  for (int k = 0; k < 3; ++k) {
-    Segment s;
-    for (int j = lo[k]; j < hi[k]; ++j) s.add(xs[j], ts[j]);
-    model_out->beta1[k] = s.slope();
-    model_out->beta0[k] = s.intercept();
-  }
-  model_out->x_break[0] = 0.5 * (xs[best_a - 1] + xs[best_a]);
-  model_out->x_break[1] = 0.5 * (xs[best_b - 1] + xs[best_b]);
-  if (sse_out) *sse_out = best;
   return OPTIMUS_OK;
 }
 

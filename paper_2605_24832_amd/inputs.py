@@ -229,7 +229,8 @@ def make_config(k: int, *, device="cpu", chunk: int | None = None, scale_down: i
     """The five benchmark configurations, seed ``BASE_SEED + k``.
 
     ``chunk`` fixes the chunk size where the configuration sweeps it (k=1: one
-    of 4/8/16/32, default 32; k=4: 64 or 128, default a seeded mix).
+    of 4/8/16/32, default 32; k=4: 64 or 128, default a seeded mix) and makes
+    the mixed batch of k=2 uniform (a diagnostic variant, not a benchmark line).
     ``scale_down`` > 1 divides batch (k=2,3) or cached length (k=1,4) so the
     same recipe gives a case the CPU oracle finishes in seconds.
     """
@@ -249,7 +250,9 @@ def make_config(k: int, *, device="cpu", chunk: int | None = None, scale_down: i
         R = max(1, 64 // scale_down)
         L = rng.randint(512, 4096 + 1, size=R)
         c = rng.choice([1, 2, 4, 8, 16, 32], size=R)
-        return make_workload("gqa_cb64", seed=seed, num_q_heads=28, num_kv_heads=4, head_dim=128,
+        if chunk is not None:      # same lengths and pages, one chunk size: isolates one kernel body
+            c = np.full(R, chunk)
+        return make_workload("gqa_cb64" if chunk is None else f"gqa_cb64_c{chunk}", seed=seed, num_q_heads=28, num_kv_heads=4, head_dim=128,
                              page_size=16, block_size=32, prefix_len=L, chunk=c,
                              shuffle_pages=True, kv_layout=kv_layout, device=device)
     if k == 3:

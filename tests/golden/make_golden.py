@@ -14,7 +14,7 @@ sys.path.insert(0, ROOT)
 import oracle  # noqa: E402
 from paper_2605_24832_amd import inputs  # noqa: E402  (seeded generators only)
 
-ROWS = [(0, 0), (0, 3), (3, 1), (7, 0), (7, 3)]     # (chunk token, query head) rows that are stored
+ROWS = [(t, h) for t in range(8) for h in range(4)]     # every (chunk token, query head) row is stored
 
 
 def compute():

@@ -16,6 +16,11 @@ def params_of(w, **kw):
     return AttnParams(**args)
 
 
+def params_of_geometry(Hq, Hkv, D, P, B, num_pages, max_pages, **kw):
+    return AttnParams(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, page_size=P, block_size=B,
+                      num_pages=num_pages, max_pages_per_req=max_pages, **kw)
+
+
 def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, **kw):
     """plan_update -> kv_append -> attn_forward on the workload's device tensors.
 

@@ -24,7 +24,7 @@ def test_oracle_reproduces_the_stored_output(oracle_mod):
     for row in doc["rows"]:
         ref = np.array([float(x) for x in row["values"]])
         np.testing.assert_allclose(out[row["token"], row["head"]], ref, rtol=1e-12, atol=1e-15)
-    assert abs(out.sum() - float(doc["sum_of_all_outputs"])) < 1e-9
+    assert len(doc["rows"]) == out.shape[0] * out.shape[1]
 
 
 @pytest.mark.gpu
@@ -36,7 +36,8 @@ def test_hip_path_matches_the_stored_output():
     w = hp.clone_workload(inputs.make_config(0, device="cpu"), device="cuda:0")
     out, _ = hp.run_hip(w)
     got = out.float().cpu().numpy().astype(np.float64)
+    ref = np.full(got.shape, np.nan)
     for row in doc["rows"]:
-        ref = np.array([float(x) for x in row["values"]])
-        assert np.abs(got[row["token"], row["head"]] - ref).max() <= 1e-2
-    assert abs(got.sum() - float(doc["sum_of_all_outputs"])) < 1e-3 * got.size
+        ref[row["token"], row["head"]] = [float(x) for x in row["values"]]
+    assert np.isfinite(ref).all(), "the fixture stores every output row"
+    hp.check_close(got, ref, what="stored oracle output of the tiny configuration")

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2605_24832_amd import commit_forward, commit_params, commit_workspace_bytes, inputs
+from paper_2605_24832_amd import commit_forward, commit_params, inputs
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -18,12 +18,11 @@ REL = 2e-5
 def run_gpu(x, vocab, thr, cu_q=None, min_commit=0):
     T = x.shape[0]
     p = commit_params(T, vocab, x.shape[1], thr, 0 if cu_q is None else len(cu_q) - 1, min_commit)
-    ws = torch.empty(commit_workspace_bytes(p) // 4 + 4, dtype=torch.float32, device=DEV)
     tok = torch.full((T,), -7, dtype=torch.int32, device=DEV)
     conf = torch.full((T,), float("nan"), dtype=torch.float32, device=DEV)
     com = torch.full((T,), -7, dtype=torch.int32, device=DEV)
     cu = None if cu_q is None else torch.as_tensor(np.asarray(cu_q, dtype=np.int32), device=DEV)
-    commit_forward(p, x, cu, tok, conf, com, ws)
+    commit_forward(p, x, cu, tok, conf, com)
     torch.cuda.synchronize()
     return tok.cpu().numpy(), conf.cpu().numpy(), com.cpu().numpy()
 
@@ -33,6 +32,7 @@ def check(oracle, x, vocab, thr, cu_q=None, min_commit=0):
     rt, rc, rcom = oracle.commit(inputs.to_bits(x), vocab, thr, cu_q, min_commit)
     np.testing.assert_array_equal(tok, rt)
     np.testing.assert_allclose(conf, rc, rtol=REL, atol=0)
+    assert ((tok >= 0) & (tok < vocab)).all()
     thr32 = np.float64(np.float32(thr))
     clear = np.abs(rc - thr32) > REL * thr32
     if cu_q is None or min_commit == 0:
@@ -84,3 +84,33 @@ def test_commit_full_size(oracle_mod):
     cu = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
     x = inputs.make_logits(int(cu[-1]), 151936, seed=62, device=DEV)
     check(oracle_mod, x, 151936, 0.9, cu, 1)
+
+
+def test_commit_masked_entries_and_one_token_requests(oracle_mod):
+    """-inf and NaN logits are entries that cannot be chosen: whole aligned 8-entry pieces of them
+    before the first finite entry (the running maximum is still -inf there), runs spanning many
+    threads' pieces, a single finite entry, fully masked rows; one-token requests under the
+    progress rule, one of them fully masked (its token is the forced fallback)."""
+    print("commit masked entries", flush=True)
+    V = 20000
+    x = inputs.make_logits(12, V, seed=71, device=DEV)
+    ninf, nan = float("-inf"), float("nan")
+    x[0, :4096] = ninf
+    x[1, 8:16384] = ninf
+    x[2, 10000:] = ninf            # the padding beyond V is NaN already
+    x[3, :V - 1] = ninf
+    x[4, ::2] = ninf
+    x[5, :V] = ninf
+    x[6, :8192] = nan
+    x[7, 1::3] = nan
+    x[8, :V] = nan
+    x[9, 5:9000] = nan
+    x[9, 9000:15000] = ninf
+    x[10, :V] = ninf
+    cu = [0, 1, 2, 5, 6, 9, 10, 11, 12]          # rows 5, 10 (fully masked) are one-token requests
+    for mc in (0, 1):
+        tok, conf, com = check(oracle_mod, x, V, 0.9, cu, mc)
+        assert np.isfinite(conf).all()
+        assert conf[5] == 0 and conf[8] == 0 and conf[10] == 0 and tok[5] == 0
+        assert tok[3] == V - 1 and conf[3] == 1.0
+    assert com[5] == 1 and com[10] == 1          # forced: the only token of their requests

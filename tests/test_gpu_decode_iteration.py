@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2605_24832_amd import (commit_forward, commit_params, commit_workspace_bytes, inputs,
+from paper_2605_24832_amd import (commit_forward, commit_params, inputs,
                                   reorg_forward)
 from tests import hip_path as hp
 
@@ -60,11 +60,10 @@ def test_two_decoding_iterations(oracle_mod):
         T = int(c.sum())
         x = inputs.make_logits(T, V, seed=900 + it, device=DEV)
         p = commit_params(T, V, x.shape[1], 0.9, R, 1)
-        wsp = torch.empty(commit_workspace_bytes(p) // 4 + 4, dtype=torch.float32, device=DEV)
         tok = torch.empty(T, dtype=torch.int32, device=DEV)
         conf = torch.empty(T, dtype=torch.float32, device=DEV)
         com = torch.empty(T, dtype=torch.int32, device=DEV)
-        commit_forward(p, x, torch.as_tensor(got["cu_q"], device=DEV), tok, conf, com, wsp)
+        commit_forward(p, x, torch.as_tensor(got["cu_q"], device=DEV), tok, conf, com)
         torch.cuda.synchronize()
         rt, rc, rcom = oracle_mod.commit(inputs.to_bits(x), V, 0.9, got["cu_q"], 1)
         np.testing.assert_array_equal(tok.cpu().numpy(), rt)
