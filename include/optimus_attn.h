@@ -164,6 +164,25 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
                          const void* v_pool, const int32_t* block_table, void* out,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* optimus_attn_forward for callers that cannot allocate or provide scratch memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and same results as optimus_attn_forward, except that the split-KV partials go
+ * to a static device array of the library instead of a workspace
+ * (optimus_attn_static_scratch_bytes() = 64 MiB, held by every GPU the library runs on until
+ * the process ends; its address on the plan's device is looked up in
+ * optimus_attn_plan_create).  The call itself allocates nothing (no hipMalloc / hipFree, no
+ * event creation: it records no timing for optimus_attn_timing_read).  A plan whose
+ * plan_update reported more workspace than that returns OPTIMUS_ERR_WORKSPACE_TOO_SMALL and
+ * nothing is launched.  The scratch is fully overwritten before it is read, so nothing has to
+ * be cleared between calls; but all calls on one GPU share it: two calls that may overlap in
+ * time (different streams, different plans or threads) race on it and must be serialised by
+ * the caller.  Planning still happens in optimus_attn_plan_update, which may allocate when a
+ * work list outgrows the plan's buffers: under graph capture, update the plan beforehand.   */
+int optimus_attn_forward_static(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* block_table, void* out,
+                                void* hip_stream);
+size_t optimus_attn_static_scratch_bytes(void);
+
 void optimus_attn_plan_destroy(optimus_attn_plan_t* plan);
 
 /* Introspection of the current work list (host). */

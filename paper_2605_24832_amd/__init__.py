@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     status_string,
+    static_scratch_bytes,
     commit_params,
     kv_write,
     commit_forward,

@@ -19,7 +19,8 @@ _lib = None
 
 EXPORTS = (
     "optimus_attn_plan_create", "optimus_attn_plan_update", "optimus_kv_append",
-    "optimus_attn_forward", "optimus_attn_plan_destroy", "optimus_attn_plan_num_work_items",
+    "optimus_attn_forward", "optimus_attn_forward_static", "optimus_attn_static_scratch_bytes",
+    "optimus_attn_plan_destroy", "optimus_attn_plan_num_work_items",
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
     "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
     "optimus_status_string", "optimus_last_hip_error",
@@ -90,6 +91,9 @@ def load_library():
                                                  ctypes.POINTER(ctypes.c_size_t)]
         lib.optimus_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.optimus_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.optimus_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        lib.optimus_attn_static_scratch_bytes.argtypes = []
+        lib.optimus_attn_static_scratch_bytes.restype = ctypes.c_size_t
         lib.optimus_attn_plan_destroy.argtypes = [vp]
         lib.optimus_attn_plan_destroy.restype = None
         lib.optimus_attn_plan_num_work_items.argtypes = [vp]
@@ -119,6 +123,10 @@ def load_library():
         lib.optimus_last_hip_error.restype = ctypes.c_char_p
         _lib = lib
     return _lib
+
+
+def static_scratch_bytes() -> int:
+    return int(load_library().optimus_attn_static_scratch_bytes())
 
 
 def status_string(status: int) -> str:
@@ -273,6 +281,13 @@ class Plan:
                                             ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_forward")
+
+    def attn_forward_static(self, q, k_pool, v_pool, block_table, out, stream=None) -> None:
+        """optimus_attn_forward_static: the split-KV partials go to the library's static scratch."""
+        rc = self._lib.optimus_attn_forward_static(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                                   _ptr(block_table), _ptr(out), _stream_ptr(stream))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_forward_static")
 
     def set_timing(self, enable: bool) -> None:
         rc = self._lib.optimus_attn_set_timing(self._h, 1 if enable else 0)

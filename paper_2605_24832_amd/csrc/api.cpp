@@ -75,6 +75,8 @@ struct optimus_attn_plan {
   // offsets (int32 units) into dev_buf
   size_t off_items = 0, off_merges = 0, off_runs = 0, off_cu_q = 0, off_prefix = 0, off_bstart = 0;
 
+  void* static_scratch = nullptr;  // this device's copy of the library's static scratch
+
   bool timing = false;
   std::vector<hipEvent_t> events;  // pairs (start, stop), created on demand
   size_t events_used = 0;
@@ -108,6 +110,11 @@ int optimus_attn_plan_create(const optimus_attn_params_t* params, int device,
       return OPTIMUS_ERR_HIP;
     }
     plan->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // address of the static scratch on this device (looked up once per device, here at set-up,
+    // so that optimus_attn_forward_static has nothing left to set up); a failure only
+    // disables that entry point
+    DeviceGuard guard(device);
+    if (guard.status() == OPTIMUS_OK) (void)static_scratch_for_current_device(device, &plan->static_scratch);
   }
   *plan_out = plan;
   return OPTIMUS_OK;
@@ -254,21 +261,11 @@ int optimus_kv_write(const optimus_attn_params_t* params, int device, void* k_po
                          (const uint16_t*)v_src, block_table, req, first_slot, n, hip_stream);
 }
 
-int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
-                         const void* v_pool, const int32_t* block_table, void* out, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
-  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  if (!plan->planned) return OPTIMUS_ERR_NOT_PLANNED;
-  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+// Shared by the two forward entry points; `workspace` holds at least hp.workspace_bytes.
+static int forward_impl(optimus_attn_plan_t* plan, const void* q, const void* k_pool, const void* v_pool,
+                        const int32_t* block_table, void* out, void* workspace, bool allow_timing,
+                        void* hip_stream) {
   const HostPlan& hp = plan->host;
-  if (hp.items.empty()) return OPTIMUS_OK;
-  if (!q || !k_pool || !v_pool || !block_table || !out) return OPTIMUS_ERR_INVALID_ARGUMENT;
-  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out | (uintptr_t)workspace) & 15)
-    return OPTIMUS_ERR_INVALID_ARGUMENT;
-  if (hp.workspace_bytes > 0 && (!workspace || workspace_bytes < hp.workspace_bytes))
-    return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
-  OPT_ON_PLAN_DEVICE(plan);
-
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   int rc = flush_upload(plan, s);
   if (rc != OPTIMUS_OK) return rc;
@@ -298,7 +295,7 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
   a.scale_log2 = scale * 1.4426950408889634f;
 
   constexpr size_t kMaxTimedForwards = 4096;
-  const bool timed = plan->timing && plan->events_used < 2 * kMaxTimedForwards;
+  const bool timed = allow_timing && plan->timing && plan->events_used < 2 * kMaxTimedForwards;
   if (timed) {
     while (plan->events.size() < plan->events_used + 2) {
       hipEvent_t e;
@@ -315,6 +312,43 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
   }
   return launch_merge(p, a, (int32_t)hp.merges.size(), hip_stream);
 }
+
+int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                         const void* v_pool, const int32_t* block_table, void* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (!plan->planned) return OPTIMUS_ERR_NOT_PLANNED;
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  const HostPlan& hp = plan->host;
+  if (hp.items.empty()) return OPTIMUS_OK;
+  if (!q || !k_pool || !v_pool || !block_table || !out) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out | (uintptr_t)workspace) & 15)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (hp.workspace_bytes > 0 && (!workspace || workspace_bytes < hp.workspace_bytes))
+    return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
+  OPT_ON_PLAN_DEVICE(plan);
+  return forward_impl(plan, q, k_pool, v_pool, block_table, out, workspace, true, hip_stream);
+}
+
+int optimus_attn_forward_static(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* block_table, void* out,
+                                void* hip_stream) {
+  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (!plan->planned) return OPTIMUS_ERR_NOT_PLANNED;
+  if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
+  const HostPlan& hp = plan->host;
+  if (hp.items.empty()) return OPTIMUS_OK;
+  if (!q || !k_pool || !v_pool || !block_table || !out) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out) & 15)
+    return OPTIMUS_ERR_INVALID_ARGUMENT;
+  if (hp.workspace_bytes > kStaticScratchBytes) return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
+  if (!plan->static_scratch) return OPTIMUS_ERR_HIP;   // its lookup failed when the plan was created
+  OPT_ON_PLAN_DEVICE(plan);
+  // no event is created here: this entry point allocates nothing, so it records no timing
+  return forward_impl(plan, q, k_pool, v_pool, block_table, out, plan->static_scratch, false, hip_stream);
+}
+
+size_t optimus_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 void optimus_attn_plan_destroy(optimus_attn_plan_t* plan) {
   if (!plan) return;

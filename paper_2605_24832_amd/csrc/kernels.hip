@@ -34,6 +34,8 @@
 //   C/D: 4 floats, rows 4*kg .. 4*kg+3, col r
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "plan_internal.h"
 
 namespace optimus {
@@ -1319,6 +1321,34 @@ __global__ __launch_bounds__(256) void kv_write_kernel(
   const int lo = max(first_slot, group * 8), hi = min(first_slot + n, group * 8 + 8);
   if (lo >= hi) return;
   write_run<D>(k_pool, v_pool, k_src, v_src, block_table, AppendRun{req, lo - first_slot, lo, hi - lo}, g);
+}
+
+// ------------------------------------------------------------------ static scratch
+// Scratch for callers that cannot allocate: the split-KV partials of optimus_attn_forward_static
+// live here instead of in a caller-provided workspace.  Every GPU the library runs on holds its
+// own copy of this array, at its own address, until the process ends.  In host code the array's
+// name is only a handle for the symbol lookup: the device address comes from
+// hipGetSymbolAddress, once per device, and that pointer is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // zero-initialised: not looked up yet
+
+int static_scratch_for_current_device(int device, void** ptr_out) {
+  if (device < 0 || device >= kMaxDevices || !ptr_out) return OPTIMUS_ERR_INVALID_ARGUMENT;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      set_hip_error((int)(e != hipSuccess ? e : hipErrorInvalidSymbol), "hipGetSymbolAddress(scratch)");
+      return OPTIMUS_ERR_HIP;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *ptr_out = g_scratch_ptr[device];
+  return OPTIMUS_OK;
 }
 
 // ------------------------------------------------------------------ launchers

@@ -128,6 +128,11 @@ int launch_upload(int32_t* dst_device, const int32_t* src_pinned_host, size_t n_
 
 void set_hip_error(int hip_err, const char* where);
 
+// Size of the library's static device scratch (one copy per GPU) and its address on `device`,
+// which must be the calling thread's current device.  The address is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+int static_scratch_for_current_device(int device, void** ptr_out);
+
 // Makes `device` the calling thread's current HIP device for the life of the object and puts
 // the caller's device back afterwards.  status() is OPTIMUS_OK or OPTIMUS_ERR_HIP.
 class DeviceGuard {
