@@ -59,7 +59,8 @@ def _load():
             build()
         _lib = ctypes.CDLL(_LIB)
         _lib.oracle_num_threads.restype = ctypes.c_int
-        for name in ("oracle_kv_append", "oracle_chunked_attention", "oracle_attention_probs",
+        for name in ("oracle_kv_append", "oracle_chunked_attention", "oracle_chunked_attention_pos",
+                     "oracle_attention_probs",
                      "oracle_partial_row"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_merge_partials.restype = None
@@ -123,8 +124,9 @@ def kv_append(p: Params, cu_q, prefix_len, block_table, k_new, v_new, k_pool, v_
 
 
 def chunked_attention(p: Params, cu_q, prefix_len, block_start, block_table, q, k_new, v_new,
-                      k_pool, v_pool) -> np.ndarray:
-    """fp64 ``[T, Hq, D]`` attention output of the whole ragged batch."""
+                      k_pool, v_pool, q_pos=None) -> np.ndarray:
+    """fp64 ``[T, Hq, D]`` attention output of the whole ragged batch.  ``q_pos``: optional
+    int32 ``[T]`` sequence positions of the chunk tokens (mask mode 1 only)."""
     lib = _load()
     cu, cu_p = _i32(cu_q)
     pl, pl_p = _i32(prefix_len)
@@ -137,8 +139,13 @@ def chunked_attention(p: Params, cu_q, prefix_len, block_start, block_table, q, 
     vp, vp_p = _u16(v_pool)
     T = int(cu[-1])
     out = np.zeros((T, p.num_q_heads, p.head_dim), dtype=np.float64)
-    rc = lib.oracle_chunked_attention(ctypes.byref(p), ctypes.c_int32(len(pl)), cu_p, pl_p, bs_p,
-                                      bt_p, q_p, kn_p, vn_p, kp_p, vp_p, _f64(out))
+    if q_pos is None:
+        pos_p = ctypes.POINTER(ctypes.c_int32)()
+    else:
+        pos, pos_p = _i32(q_pos)
+        assert len(pos) == T
+    rc = lib.oracle_chunked_attention_pos(ctypes.byref(p), ctypes.c_int32(len(pl)), cu_p, pl_p, bs_p,
+                                          bt_p, q_p, kn_p, vn_p, kp_p, vp_p, pos_p, _f64(out))
     if rc != 0:
         raise ValueError("oracle_chunked_attention: bad descriptor")
     return out

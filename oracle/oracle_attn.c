@@ -23,7 +23,10 @@
  *               is bidirectional, all c_i chunk keys visible to all c_i
  *               queries;  mode 1 (out-block streaming, Sec. 7.2, read as
  *               block-causal): chunk key k visible to chunk query j iff
- *               floor((d_i+k)/B) <= floor((d_i+j)/B);
+ *               floor((d_i+k)/B) <= floor((d_i+j)/B); with explicit sequence
+ *               positions pos[] of the chunk tokens (Sec. 4.4: the chunk is
+ *               the not yet decoded positions, which need not be contiguous)
+ *               iff floor((pos[k]-s_i)/B) <= floor((pos[j]-s_i)/B);
  *   scores    = scale * <q, K_n>,  softmax over the visible keys,
  *   output    = sum_n p_n V_n.
  *
@@ -140,11 +143,16 @@ static int gather_keys(const oracle_params_t *p, int i, int g, const int32_t *cu
 }
 
 /* Is logical key n (0..L+c-1) visible to chunk query j of a request with
- * L cached tokens and d cached tokens inside the current block?              */
-static int key_visible(const oracle_params_t *p, int L, int d, int j, int n) {
+ * L cached tokens and d cached tokens inside the current block?  pos: NULL, or
+ * the sequence positions of the request's chunk tokens (block origin s = L - d). */
+static int key_visible(const oracle_params_t *p, int L, int d, int j, int n, const int32_t *pos) {
   if (n < L) return 1;                 /* cached prefix: always */
   if (p->mask_mode == 0) return 1;     /* in-block: bidirectional chunk */
   int k = n - L;
+  if (pos) {
+    int s = L - d;
+    return (pos[k] - s) / p->block_size <= (pos[j] - s) / p->block_size;
+  }
   return (d + k) / p->block_size <= (d + j) / p->block_size;
 }
 
@@ -155,11 +163,11 @@ static int key_visible(const oracle_params_t *p, int L, int d, int j, int n) {
 static void attend_row(const oracle_params_t *p, const double *q, const double *K,
                        const double *V, int L, int dblk, int j, int lo, int hi,
                        double scale, double *s, double *m, double *l, double *o,
-                       double *p_out) {
+                       double *p_out, const int32_t *pos) {
   const int D = p->head_dim;
   double mx = -INFINITY;
   for (int n = lo; n < hi; ++n) {
-    if (!key_visible(p, L, dblk, j, n)) { s[n - lo] = -INFINITY; continue; }
+    if (!key_visible(p, L, dblk, j, n, pos)) { s[n - lo] = -INFINITY; continue; }
     double acc = 0.0;
     for (int d = 0; d < D; ++d) acc += q[d] * K[(int64_t)n * D + d];
     s[n - lo] = acc * scale;
@@ -178,15 +186,17 @@ static void attend_row(const oracle_params_t *p, const double *q, const double *
   *l = z;
 }
 
-/* Step "attention forward", whole batch.  out is fp64 [T, Hq, D].
+/* Step "attention forward", whole batch.  out is fp64 [T, Hq, D].  q_pos: NULL, or the
+ * sequence position of every chunk token (only looked at in mask mode 1).
  * q bf16 [T,Hq,D]; k_new, v_new bf16 [T,Hkv,D].  Returns 0, or -1 on a bad
  * descriptor (negative page id inside the cached range, Hq % Hkv != 0).      */
-int oracle_chunked_attention(const oracle_params_t *p, int32_t batch,
-                             const int32_t *cu_q, const int32_t *prefix_len,
-                             const int32_t *block_start, const int32_t *block_table,
-                             const uint16_t *q, const uint16_t *k_new,
-                             const uint16_t *v_new, const uint16_t *k_pool,
-                             const uint16_t *v_pool, double *out) {
+int oracle_chunked_attention_pos(const oracle_params_t *p, int32_t batch,
+                                 const int32_t *cu_q, const int32_t *prefix_len,
+                                 const int32_t *block_start, const int32_t *block_table,
+                                 const uint16_t *q, const uint16_t *k_new,
+                                 const uint16_t *v_new, const uint16_t *k_pool,
+                                 const uint16_t *v_pool, const int32_t *q_pos /* [T] or NULL */,
+                                 double *out) {
   const int D = p->head_dim, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
   if (Hkv <= 0 || Hq % Hkv != 0) return -1;
   const int G = Hq / Hkv;
@@ -212,7 +222,8 @@ int oracle_chunked_attention(const oracle_params_t *p, int32_t batch,
           int64_t t = cu_q[i] + j;
           for (int d = 0; d < D; ++d) qrow[d] = bf16_to_double(q[(t * Hq + h) * D + d]);
           double m, l;
-          attend_row(p, qrow, K, V, L, dblk, j, 0, n_keys, scale, s, &m, &l, o, NULL);
+          attend_row(p, qrow, K, V, L, dblk, j, 0, n_keys, scale, s, &m, &l, o, NULL,
+                     q_pos ? q_pos + cu_q[i] : NULL);
           for (int d = 0; d < D; ++d) out[(t * Hq + h) * D + d] = o[d] / l;
         }
       }
@@ -220,6 +231,17 @@ int oracle_chunked_attention(const oracle_params_t *p, int32_t batch,
     }
   }
   return err;
+}
+
+/* The same with the chunk taken as contiguous after the cached tokens of the block. */
+int oracle_chunked_attention(const oracle_params_t *p, int32_t batch,
+                             const int32_t *cu_q, const int32_t *prefix_len,
+                             const int32_t *block_start, const int32_t *block_table,
+                             const uint16_t *q, const uint16_t *k_new,
+                             const uint16_t *v_new, const uint16_t *k_pool,
+                             const uint16_t *v_pool, double *out) {
+  return oracle_chunked_attention_pos(p, batch, cu_q, prefix_len, block_start, block_table, q,
+                                      k_new, v_new, k_pool, v_pool, NULL, out);
 }
 
 /* Softmax probabilities of one query row (token t of request i, head h) over
@@ -249,7 +271,7 @@ int oracle_attention_probs(const oracle_params_t *p, int32_t batch, const int32_
     for (int d = 0; d < D; ++d) qrow[d] = bf16_to_double(q[(t * Hq + h) * D + d]);
     double m, l;
     attend_row(p, qrow, K, V, L, L - block_start[i], j, 0, n_keys, scale, s, &m, &l, o,
-               probs);
+               probs, NULL);
     for (int n = 0; n < n_keys; ++n) probs[n] /= l;
   }
   free(K); free(V); free(s); free(qrow); free(o);
@@ -282,7 +304,7 @@ int oracle_partial_row(const oracle_params_t *p, int32_t batch, const int32_t *c
     int64_t t = cu_q[i] + j;
     for (int d = 0; d < D; ++d) qrow[d] = bf16_to_double(q[(t * Hq + h) * D + d]);
     attend_row(p, qrow, K, V, L, L - block_start[i], j, lo, hi, scale, s, m_out, l_out,
-               o_part, NULL);
+               o_part, NULL, NULL);
   }
   free(K); free(V); free(s); free(qrow);
   return rc;

@@ -31,8 +31,10 @@ def logical_kv(w, bits_k_pool, bits_v_pool, i, g):
     return K, V
 
 
-def attention(w, bits, scale=None, mask_mode=None):
-    """``bits``: dict of uint16 arrays q, k_new, v_new, k_pool, v_pool.  -> f64 [T,Hq,D]."""
+def attention(w, bits, scale=None, mask_mode=None, chunk_mask=None):
+    """``bits``: dict of uint16 arrays q, k_new, v_new, k_pool, v_pool.  -> f64 [T,Hq,D].
+    ``chunk_mask``: optional {request: boolean [c, c] matrix, row = query, column = chunk key}
+    that replaces the computed chunk part of the mask of that request."""
     Hq, Hkv, D, B = w.num_q_heads, w.num_kv_heads, w.head_dim, w.block_size
     G = Hq // Hkv
     mode = w.mask_mode if mask_mode is None else mask_mode
@@ -51,6 +53,8 @@ def attention(w, bits, scale=None, mask_mode=None):
         if mode == 1:
             blk = (d_in + np.arange(c)) // B
             mask[:, L:] = blk[None, :] <= blk[:, None]
+        if chunk_mask is not None and i in chunk_mask:
+            mask[:, L:] = np.asarray(chunk_mask[i], dtype=bool)
         for h in range(Hq):
             g = h // G
             Kc, Vc = logical_kv(w, bits["k_pool"], bits["v_pool"], i, g)

@@ -21,6 +21,14 @@ ATTN_MUTATIONS = [
     ("block-causal mask ignores the cached part of the block", ATTN,
      "(d + k) / p->block_size <= (d + j) / p->block_size",
      "k / p->block_size <= j / p->block_size", 1),
+    ("explicit positions: comparison strict", ATTN,
+     "(pos[k] - s) / p->block_size <= (pos[j] - s) / p->block_size",
+     "(pos[k] - s) / p->block_size < (pos[j] - s) / p->block_size", 1),
+    ("explicit positions: block index counted from position 0 instead of the block origin", ATTN,
+     "(pos[k] - s) / p->block_size <= (pos[j] - s) / p->block_size",
+     "pos[k] / p->block_size <= pos[j] / p->block_size", 1),
+    ("explicit positions of the first request used for every request", ATTN,
+     "q_pos ? q_pos + cu_q[i] : NULL", "q_pos ? q_pos : NULL", 1),
     ("chunk keys gathered in reverse order", ATTN,
      "  for (int k = 0; k < c; ++k) {\n    int64_t t = cu_q[i] + k;",
      "  for (int k = 0; k < c; ++k) {\n    int64_t t = cu_q[i] + (c - 1 - k);", 1),

@@ -31,11 +31,11 @@ def oracle_params(oracle, w, **kw):
     return oracle.make_params(**args)
 
 
-def run_oracle(oracle, w, bits=None, **kw):
+def run_oracle(oracle, w, bits=None, q_pos=None, **kw):
     b = bits_of(w) if bits is None else bits
     p = oracle_params(oracle, w, **kw)
     return oracle.chunked_attention(p, w.cu_q, w.prefix_len, w.block_start, w.block_table, b["q"],
-                                    b["k_new"], b["v_new"], b["k_pool"], b["v_pool"])
+                                    b["k_new"], b["v_new"], b["k_pool"], b["v_pool"], q_pos=q_pos)
 
 
 def small(seed=1, **kw):
@@ -72,6 +72,46 @@ def test_block_causal_mask_changes_result_when_chunk_crosses_block(oracle_mod):
     assert np.abs(a[:2] - b[:2]).max() > 1e-3
     # queries 2.. sit in the second block and see everything in both modes
     np.testing.assert_array_equal(a[2:], b[2:])
+
+
+def test_explicit_positions_contiguous_case_and_mode_0(oracle_mod):
+    """Positions that follow the cached tokens of the block contiguously give the default
+    block-causal result bit for bit; in mode 0 positions are not looked at."""
+    w = small(seed=5, prefix_len=[13, 6, 20], chunk=[7, 8, 5], block_inner=[5, 6, 4], mask_mode=1)
+    pos = np.concatenate([np.arange(c) + L for L, c in zip(w.prefix_len, w.chunk)]).astype(np.int32)
+    np.testing.assert_array_equal(run_oracle(oracle_mod, w, q_pos=pos), run_oracle(oracle_mod, w))
+    rng = np.random.RandomState(5)
+    anywhere = (w.block_start.repeat(w.chunk) + rng.randint(0, 40, size=len(pos))).astype(np.int32)
+    np.testing.assert_array_equal(run_oracle(oracle_mod, w, q_pos=anywhere, mask_mode=0),
+                                  run_oracle(oracle_mod, w, mask_mode=0))
+
+
+def test_explicit_positions_hand_worked_holes(oracle_mod):
+    """Block size 4, block origin 6 (not a multiple of the block size), one cached token inside
+    the block.  Chunk tokens at sequence positions 7, 9, 10, 12: offsets 1, 3, 4, 6 from the
+    origin, i.e. blocks 0, 0, 1, 1.  Queries 0, 1 see chunk keys 0, 1; queries 2, 3 see all four.
+    The contiguous reading would put them at offsets 1, 2, 3, 4 (blocks 0, 0, 0, 1)."""
+    w = small(seed=6, block_size=4, prefix_len=[7], chunk=[4], block_inner=[1], mask_mode=1)
+    assert w.block_start[0] == 6
+    pos = np.array([7, 9, 10, 12], dtype=np.int32)
+    table = [[1, 1, 0, 0],
+             [1, 1, 0, 0],
+             [1, 1, 1, 1],
+             [1, 1, 1, 1]]
+    got = run_oracle(oracle_mod, w, q_pos=pos)
+    ref = bruteforce.attention(w, bits_of(w), chunk_mask={0: table})
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    assert np.abs(got - run_oracle(oracle_mod, w)).max() > 1e-3   # not the contiguous reading
+    # later positions in an earlier block of the chunk order: visibility follows the positions,
+    # not the order of the chunk tokens
+    pos2 = np.array([12, 7, 10, 9], dtype=np.int32)                # blocks 1, 0, 1, 0
+    table2 = [[1, 1, 1, 1],
+              [0, 1, 0, 1],
+              [1, 1, 1, 1],
+              [0, 1, 0, 1]]
+    got2 = run_oracle(oracle_mod, w, q_pos=pos2)
+    ref2 = bruteforce.attention(w, bits_of(w), chunk_mask={0: table2})
+    np.testing.assert_allclose(got2, ref2, rtol=0, atol=1e-12)
 
 
 def test_bruteforce_scale_argument(oracle_mod):
