@@ -119,7 +119,7 @@ def measure(cfg: int, chunk, steps: int, warmup: int, device: str):
     w = inputs.make_config(cfg, device=device, chunk=chunk)
     r = Runner(w, copies_for(w))
     ms, kern_ms = r.timed(steps, warmup, replan=True)
-    ms_np, _ = r.timed(max(3, steps // 2), 1, replan=False)
+    ms_np, _ = r.timed(steps, 2, replan=False)
     # host cost of planning alone
     t0 = time.perf_counter()
     for _ in range(5):
@@ -137,6 +137,24 @@ def measure(cfg: int, chunk, steps: int, warmup: int, device: str):
         "pool_copies_rotated": len(r.pools),
     }
     return w, r, res
+
+
+def roofline_of(cfg: int, w, res) -> dict:
+    """The attention kernel against the roofline that bounds the workload: MFMA bf16 dense peak
+    for the long-context configuration, HBM bandwidth for the others.  `achieved` = algorithmic
+    flops (bytes) of one launch / the kernel's mean duration by HIP events in the timed region."""
+    if cfg == 4:
+        r = {"bound": "mfma", "achieved": res["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+             "frac": res["tflops"] / MFMA_BF16_PEAK_TFLOPS}
+    else:
+        r = {"bound": "hbm", "achieved": res["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": res["hbm_GBs"] / HBM_PEAK_GBS}
+    r["traffic"] = load_traffic(w.name)
+    r["kernel"] = "attn_kernel"
+    r["kernel_ms"] = res["attn_kernel_ms"]
+    r["algorithmic_bytes_per_launch"] = res["algorithmic_bytes"]
+    r["flops_per_launch"] = res["flops"]
+    return r
 
 
 def cpu_model() -> str:
@@ -410,6 +428,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--next-only", action="store_true",
                     help="only the steps next to the attention path (commit step), as JSON; for profiling")
+    ap.add_argument("--next-rows", default="commit,reorg,selector",
+                    help="with --next-only: which of the rows to run (comma separated)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (torch copy kernel), the known-size "
                          "reference that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -424,25 +444,14 @@ def main():
         raise SystemExit("bench.py needs a GPU")
     dev = "cuda:0"
     if args.next_only:
-        print(json.dumps({"next_rows": {"commit_step": measure_commit(dev),
-                                        "reorg_step": measure_reorg(dev),
-                                        "chunk_selector": measure_selector(dev)}}))
+        rows = {"commit": ("commit_step", measure_commit), "reorg": ("reorg_step", measure_reorg),
+                "selector": ("chunk_selector", measure_selector)}
+        print(json.dumps({"next_rows": {rows[k][0]: rows[k][1](dev) for k in args.next_rows.split(",")}}))
         return
     cfg, chunk = parse_workload(args.workload)
     w, runner, res = measure(cfg, chunk, args.steps, args.warmup, dev)
 
-    bound_mfma = cfg == 4
-    if bound_mfma:
-        roofline = {"bound": "mfma", "achieved": res["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": res["tflops"] / MFMA_BF16_PEAK_TFLOPS}
-    else:
-        roofline = {"bound": "hbm", "achieved": res["hbm_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": res["hbm_GBs"] / HBM_PEAK_GBS}
-    roofline["traffic"] = load_traffic(w.name)
-    roofline["kernel"] = "attn_kernel"
-    roofline["kernel_ms"] = res["attn_kernel_ms"]
-    roofline["algorithmic_bytes_per_launch"] = res["algorithmic_bytes"]
-    roofline["flops_per_launch"] = res["flops"]
+    roofline = roofline_of(cfg, w, res)
 
     line = {
         "metric": "query tokens/s, chunked block-diffusion attention step (plan + KV append + attention + merge)",
@@ -486,13 +495,22 @@ def main():
             if name == args.workload:
                 continue
             c2, ch2 = parse_workload(name)
-            w2, r2, o = measure(c2, ch2, max(5, args.steps // 3), 3, dev)
+            w2, r2, o = measure(c2, ch2, max(20, args.steps), max(5, args.warmup), dev)
+            o["roofline"] = roofline_of(c2, w2, o)
             o["roofline_frac_hbm"] = o["hbm_GBs"] / HBM_PEAK_GBS
             o["roofline_frac_mfma_bf16"] = o["tflops"] / MFMA_BF16_PEAK_TFLOPS
+            if not args.no_cpu_baseline:
+                o["cpu_baseline"], o["parity_vs_oracle"] = cpu_baseline(w2, r2, budget_s=12.0)
             others.append(o)
             del w2, r2
             torch.cuda.empty_cache()
         line["other_configs"] = others
+        # the metric's second leg (MFMA utilisation at large chunks): the long-context
+        # configuration at c = 128, same object layout as `roofline`
+        for o in others:
+            if o["workload"] == "longctx_b4_c128":
+                line["roofline_mfma"] = dict(o["roofline"], workload=o["workload"],
+                                             parity_vs_oracle=o.get("parity_vs_oracle"))
         line["mfma_probe"] = measure_mfma_probe(dev)
         line["next_rows"] = {"commit_step": measure_commit(dev), "reorg_step": measure_reorg(dev),
                              "chunk_selector": measure_selector(dev)}

@@ -164,6 +164,19 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
                          const void* v_pool, const int32_t* block_table, void* out,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* optimus_attn_forward with the sequence positions of the chunk tokens (Sec. 4.4: the chunk is
+ * rebuilt every step from the positions not yet decoded, which need not be contiguous; Sec. 7.2
+ * out-block streaming lets it cross a block boundary).  q_pos: int32 [T] device memory, e.g.
+ * q_pos_out of optimus_reorg_forward, or NULL (= optimus_attn_forward).  Only mask_mode 1 looks
+ * at it: chunk key k is visible to chunk query j iff
+ * (q_pos[k] - s_i) / B <= (q_pos[j] - s_i) / B.  Preconditions: q_pos >= s_i and non-decreasing
+ * within a request's chunk (the order optimus_reorg_forward emits); for other orders the
+ * visible keys are taken to be the first n chunk keys, n = number of chunk keys whose position
+ * lies before the end of the query's block.  No memory access depends on a position value.  */
+int optimus_attn_forward_pos(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                             const void* v_pool, const int32_t* block_table, const int32_t* q_pos,
+                             void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* optimus_attn_forward for callers that cannot allocate or provide scratch memory: code under
  * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
  * same kernels and same results as optimus_attn_forward, except that the split-KV partials go

@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = (
     "optimus_attn_plan_create", "optimus_attn_plan_update", "optimus_kv_append",
-    "optimus_attn_forward", "optimus_attn_forward_static", "optimus_attn_static_scratch_bytes",
+    "optimus_attn_forward", "optimus_attn_forward_pos", "optimus_attn_forward_static", "optimus_attn_static_scratch_bytes",
     "optimus_attn_plan_destroy", "optimus_attn_plan_num_work_items",
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
     "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
@@ -91,6 +91,7 @@ def load_library():
                                                  ctypes.POINTER(ctypes.c_size_t)]
         lib.optimus_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.optimus_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.optimus_attn_forward_pos.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.optimus_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.optimus_attn_static_scratch_bytes.argtypes = []
         lib.optimus_attn_static_scratch_bytes.restype = ctypes.c_size_t
@@ -274,11 +275,19 @@ class Plan:
         if rc != 0:
             raise OptimusError(rc, "optimus_kv_append")
 
-    def attn_forward(self, q, k_pool, v_pool, block_table, out, workspace=None, stream=None) -> None:
+    def attn_forward(self, q, k_pool, v_pool, block_table, out, workspace=None, stream=None,
+                     q_pos=None) -> None:
+        """optimus_attn_forward, or optimus_attn_forward_pos when ``q_pos`` (int32 device tensor) is given."""
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-        rc = self._lib.optimus_attn_forward(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool),
-                                            _ptr(block_table), _ptr(out), _ptr(workspace),
-                                            ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
+        if q_pos is None:
+            rc = self._lib.optimus_attn_forward(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                                _ptr(block_table), _ptr(out), _ptr(workspace),
+                                                ctypes.c_size_t(ws_bytes), _stream_ptr(stream))
+        else:
+            rc = self._lib.optimus_attn_forward_pos(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                                    _ptr(block_table), _ptr(q_pos), _ptr(out),
+                                                    _ptr(workspace), ctypes.c_size_t(ws_bytes),
+                                                    _stream_ptr(stream))
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_forward")
 

@@ -263,8 +263,8 @@ int optimus_kv_write(const optimus_attn_params_t* params, int device, void* k_po
 
 // Shared by the two forward entry points; `workspace` holds at least hp.workspace_bytes.
 static int forward_impl(optimus_attn_plan_t* plan, const void* q, const void* k_pool, const void* v_pool,
-                        const int32_t* block_table, void* out, void* workspace, bool allow_timing,
-                        void* hip_stream) {
+                        const int32_t* block_table, const int32_t* q_pos, void* out, void* workspace,
+                        bool allow_timing, void* hip_stream) {
   const HostPlan& hp = plan->host;
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   int rc = flush_upload(plan, s);
@@ -280,6 +280,8 @@ static int forward_impl(optimus_attn_plan_t* plan, const void* q, const void* k_
   a.merges = reinterpret_cast<const MergeItem*>(d + plan->off_merges);
   a.prefix_len = d + plan->off_prefix;
   a.block_start = d + plan->off_bstart;
+  a.cu_q = d + plan->off_cu_q;
+  a.q_pos = p.mask_mode == 1 ? q_pos : nullptr;
   a.out = out;
   a.ws_o = reinterpret_cast<float*>(workspace);
   a.ws_ml = a.ws_o ? a.ws_o + (size_t)hp.part_rows * p.head_dim : nullptr;
@@ -316,6 +318,13 @@ static int forward_impl(optimus_attn_plan_t* plan, const void* q, const void* k_
 int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
                          const void* v_pool, const int32_t* block_table, void* out, void* workspace,
                          size_t workspace_bytes, void* hip_stream) {
+  return optimus_attn_forward_pos(plan, q, k_pool, v_pool, block_table, nullptr, out, workspace,
+                                  workspace_bytes, hip_stream);
+}
+
+int optimus_attn_forward_pos(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
+                             const void* v_pool, const int32_t* block_table, const int32_t* q_pos,
+                             void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (!plan->planned) return OPTIMUS_ERR_NOT_PLANNED;
   if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
@@ -327,7 +336,7 @@ int optimus_attn_forward(optimus_attn_plan_t* plan, const void* q, const void* k
   if (hp.workspace_bytes > 0 && (!workspace || workspace_bytes < hp.workspace_bytes))
     return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
   OPT_ON_PLAN_DEVICE(plan);
-  return forward_impl(plan, q, k_pool, v_pool, block_table, out, workspace, true, hip_stream);
+  return forward_impl(plan, q, k_pool, v_pool, block_table, q_pos, out, workspace, true, hip_stream);
 }
 
 int optimus_attn_forward_static(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
@@ -345,7 +354,8 @@ int optimus_attn_forward_static(optimus_attn_plan_t* plan, const void* q, const 
   if (!plan->static_scratch) return OPTIMUS_ERR_HIP;   // its lookup failed when the plan was created
   OPT_ON_PLAN_DEVICE(plan);
   // no event is created here: this entry point allocates nothing, so it records no timing
-  return forward_impl(plan, q, k_pool, v_pool, block_table, out, plan->static_scratch, false, hip_stream);
+  return forward_impl(plan, q, k_pool, v_pool, block_table, nullptr, out, plan->static_scratch, false,
+                      hip_stream);
 }
 
 size_t optimus_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }

@@ -3,18 +3,22 @@
 // Confidence = largest softmax probability of the position's logit row, token = first index
 // attaining it; -inf and NaN logits are entries that cannot be chosen.
 //
-// HBM-bound scan of the logits with a co-critical exponential per entry.  One workgroup of
-// 1024 threads owns one row (no partial results leave the workgroup): every thread walks
-// its 16-byte pieces with eight loads in flight and keeps an online (max, sum of exp, first
-// argmax); the threads are joined through the wave and LDS and the row's token, confidence
-// and commit flag are stored directly.  A second, tiny kernel applies the per-request progress rule.
-//
-// Arithmetic per entry: unpack, max (v_max3 over a piece), one fma, one exp2, one add.  The
-// exponent is fma(x, log2 e, -r) with r = fl(m * log2 e) the reference in log2 units, which
-// the joins carry along, so no rounding of m * log2 e enters the result: the confidence is
-// 2^(fma(M, log2 e, -R)) / S for the row's maximum M and the final reference R.
-// -inf entries add exp2(-inf) = 0; a piece whose sum comes out NaN (a NaN entry) is summed
-// again with NaN entries read as -inf.  +inf entries are outside the definition (no access
+// HBM-bound scan of the logits with a co-critical exponential per entry (about five vector
+// instructions per entry, one of them a quarter-rate v_exp_f32: at 152K entries per row the
+// vector unit and the memory system are busy for about the same time).  One workgroup of 1024
+// threads owns one row, so no partial result leaves the workgroup.  A thread walks its 16-byte
+// pieces eight at a time (eight loads in flight) and keeps
+//   m     largest entry so far (bookkeeping for the token only),
+//   base  first of its pieces that holds m,
+//   r     reference of the exponentials in log2 units, s = sum of 2^(x log2 e - r).
+// The reference is set from the thread's first piece and then followed lazily: it only moves
+// (rare path, the eight pieces are summed again) when the maximum has grown more than 2^64
+// beyond it, so the common path is unpack, max, fma, exp2, add and nothing else; the result
+// 2^(M log2 e - R) / S does not depend on where the reference sits.  Entries that are -inf add
+// exp2(-inf) = 0; when a sum comes out NaN (a NaN entry) the eight pieces are summed again
+// with NaN entries skipped.  The threads are joined through the wave and LDS; the winning
+// piece is read once more to find the first entry equal to the maximum.  A second, tiny kernel
+// applies the per-request progress rule.  +inf entries are outside the definition (no access
 // depends on a value, so they cannot cause one out of bounds).
 #include <hip/hip_runtime.h>
 
@@ -26,114 +30,161 @@
 namespace optimus {
 
 typedef unsigned int u32x4c __attribute__((ext_vector_type(4)));
-constexpr int kRowThreads = 1024;
+constexpr int kRowThreads = 512;
 constexpr int kPiece = 8;                       // bf16 per 16-byte load
 constexpr int kInflight = 8;                    // 16-byte loads in flight per thread
+constexpr int kRound = kInflight * kRowThreads; // pieces one workgroup takes per round
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kRefSlack = 64.0f;              // the reference may trail the maximum by 2^64
 constexpr uint32_t kNegInfPair = 0xff80ff80u;   // two bf16 -inf
 
-struct RowState { float m, r, s; int32_t idx; };   // LDS record of one wave's result
+struct RowState { float m, r, s; int32_t base; };   // LDS record of one wave's result
 
 __device__ __forceinline__ bool is_nan_bits(float x) {   // the build assumes no NaN: compare bit patterns
   return (__float_as_uint(x) & 0x7fffffffu) > 0x7f800000u;
 }
 
 // Join with the state of lane (lane ^ off); plain scalars so that everything stays in registers.
-__device__ __forceinline__ void join_xor(float& m, float& r, float& s, int32_t& idx, int off) {
+// Equal maxima keep the smaller piece (pieces of different threads are disjoint index ranges).
+__device__ __forceinline__ void join_xor(float& m, float& r, float& s, int32_t& base, int off) {
   const float bm = __shfl_xor(m, off, 64), br = __shfl_xor(r, off, 64), bs = __shfl_xor(s, off, 64);
-  const int32_t bi = __shfl_xor(idx, off, 64);
-  const bool b_wins = bm > m || (bm == m && bi < idx);
+  const int32_t bb = __shfl_xor(base, off, 64);
+  const bool b_wins = bm > m || (bm == m && bb < base);
   const float R = fmaxf(r, br);
   // r = -inf on both sides: nothing summed yet (the difference would be NaN)
   s = R == -INFINITY ? 0.f : s * __builtin_amdgcn_exp2f(r - R) + bs * __builtin_amdgcn_exp2f(br - R);
   m = b_wins ? bm : m;
-  idx = b_wins ? bi : idx;
+  base = b_wins ? bb : base;
   r = R;
 }
 
-// 8 waves per SIMD: two rows resident per compute unit (at most 64 vector registers)
-__global__ __launch_bounds__(kRowThreads, 8) void commit_row_kernel(
-    const uint16_t* __restrict__ logits, int vocab, int64_t row_stride, float threshold,
-    int32_t* __restrict__ token_out, float* __restrict__ conf_out, int32_t* __restrict__ commit_out) {
-  const int t = blockIdx.x;
-  const uint16_t* row = logits + (int64_t)t * row_stride;
-  const int n_pieces = (vocab + kPiece - 1) / kPiece;
-  // m: largest entry so far (-inf: none), r = fl(m * log2 e), s = sum of 2^(x log2 e - r),
-  // idx = first index attaining m
-  float pm = -INFINITY, pr = -INFINITY, ps = 0.f;
-  int32_t pidx = 0x7fffffff;
-  for (int p0 = threadIdx.x; p0 < n_pieces; p0 += kInflight * kRowThreads) {
-    // rows are padded to a multiple of 8 entries, so a piece that starts inside the row is
-    // readable as a whole; pieces past the row read as -inf and change nothing
-    u32x4c raw[kInflight];
+__device__ __forceinline__ void unpack(const u32x4c raw, float (&x)[kPiece]) {
 #pragma unroll
-    for (int u = 0; u < kInflight; ++u) {
-      const int pc = p0 + u * kRowThreads;
-      raw[u] = pc < n_pieces ? __builtin_nontemporal_load(reinterpret_cast<const u32x4c*>(row) + pc)   // read once
+  for (int e = 0; e < 4; ++e) {
+    x[2 * e] = __uint_as_float(raw[e] << 16);
+    x[2 * e + 1] = __uint_as_float(raw[e] & 0xffff0000u);
+  }
+}
+
+// Entries at or beyond the row's end read as -inf.
+__device__ __forceinline__ void mask_row_end(float (&x)[kPiece], int base, int vocab) {
+  if (base + kPiece > vocab) {
+#pragma unroll
+    for (int e = 0; e < kPiece; ++e)
+      if (base + e >= vocab) x[e] = -INFINITY;
+  }
+}
+
+// One round of a thread: pieces p0, p0 + 1024, ... (kInflight of them).  CHECKED: the round may
+// reach past the row (its last one); otherwise every piece lies inside the row.
+template <bool CHECKED>
+__device__ __forceinline__ void scan_round(const u32x4c* __restrict__ row, int p0, int n_pieces, int vocab,
+                                           float& m, float& r, float& s, int32_t& best_base) {
+  u32x4c raw[kInflight];
+#pragma unroll
+  for (int u = 0; u < kInflight; ++u) {
+    const int pc = p0 + u * kRowThreads;
+    if (CHECKED)
+      raw[u] = pc < n_pieces ? __builtin_nontemporal_load(row + pc)   // read once
                              : u32x4c{kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair};
-    }
+    else
+      raw[u] = __builtin_nontemporal_load(row + pc);
+  }
+  if (r == -INFINITY) {
+    // no reference yet (start of the row, or only masked entries so far): take it from this
+    // thread's first piece of the round; v_max skips NaN operands
+    float x[kPiece];
+    unpack(raw[0], x);
+    if (CHECKED) mask_row_end(x, p0 * kPiece, vocab);
+    const float c0 = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    if (!is_nan_bits(c0)) r = c0 * kLog2e;    // still -inf if the piece is masked
+  }
+  const float s_before = s;
+  float nr = r == -INFINITY ? 0.f : -r;       // exp2(-inf + 0) = 0 for masked entries
+#pragma unroll
+  for (int u = 0; u < kInflight; ++u) {
+    const int base = (p0 + u * kRowThreads) * kPiece;
+    if (CHECKED && __builtin_amdgcn_ballot_w64(base < vocab) == 0) continue;   // the whole wave is past the row
+    float x[kPiece];
+    unpack(raw[u], x);
+    if (CHECKED) mask_row_end(x, base, vocab);
+    // v_max returns the other operand when one is NaN: cm is the largest non-NaN entry
+    const float cm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    const float m_new = fmaxf(m, cm);         // m is never NaN, so neither is m_new
+    best_base = m_new > m ? base : best_base; // strict: the earlier piece keeps a tie
+    m = m_new;
+#pragma unroll
+    for (int e = 0; e < kPiece; ++e) s += __builtin_amdgcn_exp2f(fmaf(x[e], kLog2e, nr));
+  }
+  // Rare path: a NaN entry reached the sum, or the maximum has run away from the reference
+  // (also: the first unmasked entries of a row whose first piece was masked).  Sum the round
+  // again from its start with the reference at the maximum and NaN entries skipped.
+  const bool redo = is_nan_bits(s) || (m != -INFINITY && (r == -INFINITY || fmaf(m, kLog2e, nr) > kRefSlack));
+  if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+    const float r_new = m == -INFINITY ? r : fmaxf(r, m * kLog2e);
+    s = r == -INFINITY ? 0.f : s_before * __builtin_amdgcn_exp2f(r - r_new);
+    r = r_new;
+    nr = r == -INFINITY ? 0.f : -r;
 #pragma unroll
     for (int u = 0; u < kInflight; ++u) {
       const int base = (p0 + u * kRowThreads) * kPiece;
-      if (__builtin_amdgcn_ballot_w64(base < vocab) == 0) continue;   // the whole wave is past the row
-      uint32_t xb[kPiece];
       float x[kPiece];
+      unpack(raw[u], x);
+      if (CHECKED) mask_row_end(x, base, vocab);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        xb[2 * e] = raw[u][e] << 16;
-        xb[2 * e + 1] = raw[u][e] & 0xffff0000u;
-      }
-      if (base + kPiece > vocab) {   // the row's last piece (or one past the row)
-#pragma unroll
-        for (int e = 0; e < kPiece; ++e)
-          if (base + e >= vocab) xb[e] = 0xff800000u;
-      }
-#pragma unroll
-      for (int e = 0; e < kPiece; ++e) x[e] = __uint_as_float(xb[e]);
-      // v_max returns the other operand when one is NaN, so cm is the largest non-NaN entry
-      // (NaN only if all eight are)
-      const float cm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      const bool raise = cm > pm && !is_nan_bits(cm);   // strict: the earlier piece keeps a tie
-      if (__builtin_amdgcn_ballot_w64(raise) != 0) {   // rare after the first pieces of a row
-        // first entry equal to cm, compared as bit patterns (+0 and -0 are equal)
-        const uint32_t cmb = __float_as_uint(cm);
-        int ci = kPiece - 1;
-#pragma unroll
-        for (int e = kPiece - 2; e >= 0; --e)
-          ci = (xb[e] == cmb || ((xb[e] | cmb) & 0x7fffffffu) == 0u) ? e : ci;
-        const float r_new = raise ? cm * kLog2e : pr;
-        ps = pr == -INFINITY ? 0.f : ps * __builtin_amdgcn_exp2f(pr - r_new);
-        pidx = raise ? base + ci : pidx;
-        pm = raise ? cm : pm;
-        pr = r_new;
-      }
-      const float ref = pr == -INFINITY ? 0.f : -pr;   // nothing finite yet: exp2(-inf + 0) = 0
-      float add = 0.f;
-#pragma unroll
-      for (int e = 0; e < kPiece; ++e) add += __builtin_amdgcn_exp2f(fmaf(x[e], kLog2e, ref));
-      if (__builtin_amdgcn_ballot_w64(is_nan_bits(add)) != 0) {   // some entry is NaN: it counts as -inf
-        add = 0.f;
-#pragma unroll
-        for (int e = 0; e < kPiece; ++e)
-          add += is_nan_bits(x[e]) ? 0.f : __builtin_amdgcn_exp2f(fmaf(x[e], kLog2e, ref));
-      }
-      ps += add;
+      for (int e = 0; e < kPiece; ++e)
+        s += is_nan_bits(x[e]) ? 0.f : __builtin_amdgcn_exp2f(fmaf(x[e], kLog2e, nr));
     }
   }
+}
+
+// 8 waves per SIMD: two rows resident per compute unit (at most 64 vector registers)
+__global__ __launch_bounds__(kRowThreads, 4) void commit_row_kernel(
+    const uint16_t* __restrict__ logits, int vocab, int64_t row_stride, float threshold,
+    int32_t* __restrict__ token_out, float* __restrict__ conf_out, int32_t* __restrict__ commit_out) {
+  const int t = blockIdx.x;
+  // rows are padded to a multiple of 8 entries, so a piece that starts inside the row is
+  // readable as a whole
+  const u32x4c* row = reinterpret_cast<const u32x4c*>(logits + (int64_t)t * row_stride);
+  const int n_pieces = (vocab + kPiece - 1) / kPiece;
+  float pm = -INFINITY, pr = -INFINITY, ps = 0.f;
+  int32_t pbase = 0x7fffffff;
+  // all rounds but the last lie inside the row for every thread; the last one is checked
+  const int full_rounds = (n_pieces - 1) / kRound;
+  int p0 = threadIdx.x;
+  for (int i = 0; i < full_rounds; ++i, p0 += kRound)
+    scan_round<false>(row, p0, n_pieces, vocab, pm, pr, ps, pbase);
+  scan_round<true>(row, p0, n_pieces, vocab, pm, pr, ps, pbase);
+
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) join_xor(pm, pr, ps, pidx, off);
+  for (int off = 32; off >= 1; off >>= 1) join_xor(pm, pr, ps, pbase, off);
   __shared__ RowState sm[kRowThreads / 64];
-  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = RowState{pm, pr, ps, pidx};
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = RowState{pm, pr, ps, pbase};
   __syncthreads();
   if (threadIdx.x < 64) {
     const RowState w = sm[threadIdx.x & (kRowThreads / 64 - 1)];
-    pm = w.m; pr = w.r; ps = w.s; pidx = w.idx;
+    pm = w.m; pr = w.r; ps = w.s; pbase = w.base;
 #pragma unroll
-    for (int off = kRowThreads / 128; off >= 1; off >>= 1) join_xor(pm, pr, ps, pidx, off);
+    for (int off = kRowThreads / 128; off >= 1; off >>= 1) join_xor(pm, pr, ps, pbase, off);
     if (threadIdx.x == 0) {
       const bool none = pm == -INFINITY;   // every entry masked
+      int token = 0;
+      if (!none) {
+        // first entry of the winning piece equal to the maximum, compared as bit patterns
+        // (+0 and -0 are equal); entries beyond the row are never equal to it: they are the
+        // padding, and the maximum was taken over the row only, so stop at the row's end
+        const u32x4c raw = row[pbase / kPiece];
+        const uint32_t mb = __float_as_uint(pm);
+        int ci = kPiece - 1;
+#pragma unroll
+        for (int e = kPiece - 2; e >= 0; --e) {
+          const uint32_t xb = (e & 1) ? (raw[e / 2] & 0xffff0000u) : (raw[e / 2] << 16);
+          ci = (xb == mb || ((xb | mb) & 0x7fffffffu) == 0u) ? e : ci;
+        }
+        token = min(pbase + ci, vocab - 1);
+      }
       const float conf = none ? 0.f : __builtin_amdgcn_exp2f(fmaf(pm, kLog2e, -pr)) / ps;
-      token_out[t] = none ? 0 : pidx;
+      token_out[t] = token;
       conf_out[t] = conf;
       commit_out[t] = conf > threshold ? 1 : 0;
     }

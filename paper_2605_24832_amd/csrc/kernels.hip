@@ -86,6 +86,30 @@ __device__ __forceinline__ float xor_sum(float v) {
   return x + y;
 }
 
+// Block-causal mode (mask_mode 1): first logical key that chunk query j of the item's request may
+// not see.  Without explicit positions the chunk follows the d_in cached tokens of the block
+// contiguously.  With positions (q_pos, non-decreasing within a request's chunk): the chunk keys
+// whose position lies before the end of query j's block, counted (for non-decreasing positions
+// these are exactly the keys of blocks up to the query's).
+__device__ __forceinline__ int block_causal_end(const KernelArgs& a, const optimus_work_item_t& it, int L,
+                                                int d_in, int j) {
+  const int B = a.block_size;
+  if (!a.q_pos) return L + ((d_in + j) / B + 1) * B - d_in;
+  const int32_t* pos = a.q_pos + it.q_token0;
+  const int c = a.cu_q[it.req + 1] - it.q_token0;
+  const int s = L - d_in;
+  const int end_pos = s + ((pos[j] - s) / B + 1) * B;   // first position of the next block
+  int n = 0;
+  for (int k = 0; k < c; ++k) n += pos[k] < end_pos ? 1 : 0;
+  return L + n;
+}
+// First key any query of the request might not see (wave-uniform); with explicit positions
+// every tile that holds chunk keys takes the masked path.
+__device__ __forceinline__ int block_causal_min(const KernelArgs& a, int L, int d_in) {
+  const int B = a.block_size;
+  return a.q_pos ? L : L + (d_in / B + 1) * B - d_in;
+}
+
 template <int D>
 struct KvTile {
   bf16x8 k[2][D / 32];   // [16-key half][d step of 32]
@@ -289,10 +313,10 @@ __device__ __forceinline__ void split_wave_body(const KernelArgs& a, const optim
       qreg[nt][s] = __builtin_bit_cast(bf16x8, x);
     }
     // block-causal variant: chunk key k visible iff (d_in+k)/B <= (d_in+j)/B
-    vis_end[nt] = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + j) / a.block_size + 1) * a.block_size - d_in;
+    vis_end[nt] = a.mask_mode == 0 ? INT32_MAX : block_causal_end(a, it, L, d_in, j);
   }
   // first key any row of the request might not see (uniform)
-  const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
+  const int vis_min = a.mask_mode == 0 ? INT32_MAX : block_causal_min(a, L, d_in);
   const int mask_from = min(it.kv_end, vis_min);
 
   SoftmaxState<D, NT> st;
@@ -520,9 +544,9 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
       if (!valid) x = u32x4{0u, 0u, 0u, 0u};
       qreg[nt][s] = __builtin_bit_cast(bf16x8, x);
     }
-    vis_end[nt] = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + j) / a.block_size + 1) * a.block_size - d_in;
+    vis_end[nt] = a.mask_mode == 0 ? INT32_MAX : block_causal_end(a, it, L, d_in, j);
   }
-  const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
+  const int vis_min = a.mask_mode == 0 ? INT32_MAX : block_causal_min(a, L, d_in);
   const int mask_from = min(it.kv_end, vis_min);
   const bool wave_has_rows = wave * NT * 16 < it.row_count;  // uniform per wave
 
@@ -832,8 +856,8 @@ __device__ __forceinline__ void wide_tile_body(const KernelArgs& a, const optimu
     L = a.prefix_len[it.req];
     d_in = L - a.block_start[it.req];
   }
-  const int vis_end = a.mask_mode == 0 ? INT32_MAX : L + ((d_in + jq) / a.block_size + 1) * a.block_size - d_in;
-  const int vis_min = a.mask_mode == 0 ? INT32_MAX : L + (d_in / a.block_size + 1) * a.block_size - d_in;
+  const int vis_end = a.mask_mode == 0 ? INT32_MAX : block_causal_end(a, it, L, d_in, jq);
+  const int vis_min = a.mask_mode == 0 ? INT32_MAX : block_causal_min(a, L, d_in);
   const int mask_from = min(it.kv_end, vis_min);
   const int lim = min(it.kv_end, vis_end);
   const bool wave_has_rows = wave * 32 < it.row_count;  // uniform per wave

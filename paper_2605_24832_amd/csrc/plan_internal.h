@@ -96,6 +96,8 @@ struct KernelArgs {
   const MergeItem* merges;
   const int32_t* prefix_len;
   const int32_t* block_start;
+  const int32_t* cu_q;    // [batch + 1]
+  const int32_t* q_pos;   // [T] sequence positions of the chunk tokens, or null (mask mode 1 only)
   void* out;
   float* ws_o;    // [part_rows, D]
   float* ws_ml;   // [part_rows, 2]  (running max in log2 units, sum)

@@ -288,6 +288,19 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
         if (lane_len[x] > d) pos[lane_first[x] + d] = next++;
   }
   hp.items.resize(n_items);
+  // Where the item of cost rank r of a lane goes (depth in the lane).  The workgroups of a launch
+  // are handed to the compute units of a die round-robin, two per unit, so the items at depths d
+  // and d + C of a lane (C = units per die) share a unit for their whole life, and a unit
+  // works through the tiles of its two items at a rate that hardly depends on how they are
+  // split between the two (measured per-unit time stamps on a mixed-chunk batch: unit loads
+  // differed by 2x and the kernel lasted as long as the most loaded unit).  So the second C items of a
+  // lane are placed in ascending order: the costliest item shares its unit with the cheapest
+  // of the first 2C.  Later items start as units free up and keep the costliest-first order.
+  const size_t units = (size_t)std::max(1, num_cus / kNumXcd);
+  auto depth_of_rank = [units](size_t r, size_t lane_items) {
+    const size_t first_round = std::min(lane_items, 2 * units);
+    return (r >= units && r < first_round) ? units + (first_round - 1 - r) : r;
+  };
   size_t lane_fill[kNumXcd] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int32_t gi : order) {
     const Group& gr = groups[gi];
@@ -304,7 +317,7 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
         const MergeItem& m = hp.merges[hp.req_first_merge[gr.req] + gr.kv_head * gr.n_row_tiles + rt];
         it.part_row = m.first_part_row + gr.split * rc;
       }
-      hp.items[pos[lane_first[x] + lane_fill[x]++]] = it;
+      hp.items[pos[lane_first[x] + depth_of_rank(lane_fill[x]++, lane_len[x])]] = it;
     }
   }
   hp.part_rows = part_rows;

@@ -21,7 +21,7 @@ def params_of_geometry(Hq, Hkv, D, P, B, num_pages, max_pages, **kw):
                       num_pages=num_pages, max_pages_per_req=max_pages, **kw)
 
 
-def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, **kw):
+def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, q_pos=None, **kw):
     """plan_update -> kv_append -> attn_forward on the workload's device tensors.
 
     Returns (out tensor on device, plan).  The pools of ``w`` are modified by the append.
@@ -41,7 +41,8 @@ def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, **
                      dtype=torch.float32 if out_dtype == 1 else torch.bfloat16, device=w.q.device)
     if append:
         plan.kv_append(w.k_pool, w.v_pool, w.k_new, w.v_new, bt)
-    plan.attn_forward(w.q, w.k_pool, w.v_pool, bt, out, ws)
+    pos = None if q_pos is None else torch.as_tensor(np.asarray(q_pos, dtype=np.int32), device=w.q.device)
+    plan.attn_forward(w.q, w.k_pool, w.v_pool, bt, out, ws, q_pos=pos)
     torch.cuda.synchronize()
     return out, plan
 
@@ -59,7 +60,7 @@ def host_bits(w):
     return {k: inputs.to_bits(getattr(w, k)) for k in ("q", "k_new", "v_new", "k_pool", "v_pool")}
 
 
-def run_oracle(oracle, w, bits=None, requests=None, kv_heads=None, **kw):
+def run_oracle(oracle, w, bits=None, requests=None, kv_heads=None, q_pos=None, **kw):
     """Oracle output for the whole batch, or for a subset of requests and/or kv-head groups.
 
     A request's rows do not depend on the rest of the batch and a kv-head group
@@ -90,7 +91,8 @@ def run_oracle(oracle, w, bits=None, requests=None, kv_heads=None, **kw):
     cu = np.zeros(len(req) + 1, dtype=np.int32)
     cu[1:] = np.cumsum(w.chunk[req])
     out = oracle.chunked_attention(p, cu, w.prefix_len[req], w.block_start[req],
-                                   w.block_table[req], q, kn, vn, kp, vp)
+                                   w.block_table[req], q, kn, vn, kp, vp,
+                                   q_pos=None if q_pos is None else np.asarray(q_pos, dtype=np.int32)[tok])
     return out, tok, qh
 
 

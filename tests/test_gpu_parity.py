@@ -174,6 +174,51 @@ def test_block_causal_mode(oracle_mod):
                 tuning=dict(target_items=1 << 20, min_split_tokens=32, max_split_tokens=32))
 
 
+@pytest.mark.parametrize("split", [0, 32])
+def test_block_causal_mode_with_explicit_positions(oracle_mod, split):
+    """mask_mode 1 with the sequence positions of the chunk tokens (Sec. 4.4: the chunk is the
+    positions not yet decoded, with holes where tokens were decoded out of order): every body
+    (7, 20 and 32 tokens x 4 heads per kv head = 28, 80, 128 rows; 2 x 4 = 8 rows), chunks that
+    cross a block boundary, a block origin that is not a multiple of the block size."""
+    _say(f"mask mode 1, explicit positions, split {split}")
+    B = 32
+    L = np.array([100, 40, 0, 500, 77])
+    d_in = np.array([20, 0, 0, 30, 13])
+    c = np.array([32, 20, 7, 2, 32])
+    w = inputs.make_workload("obs_pos", seed=59, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                             page_size=16, block_size=B, prefix_len=L, chunk=c, block_inner=d_in,
+                             mask_mode=1, device=DEV)
+    rng = np.random.RandomState(59)
+    pos = []
+    for i in range(len(L)):
+        s = int(L[i] - d_in[i])
+        # the chunk = the first c_i not decoded positions among the 2B after the origin: a random
+        # subset of d_in positions is decoded (cached), the chunk skips them
+        decoded = set(rng.choice(2 * B, size=int(d_in[i]), replace=False).tolist())
+        free = [s + x for x in range(3 * B) if x not in decoded]
+        pos += free[:int(c[i])]
+    tuning = None if split == 0 else dict(target_items=1 << 20, min_split_tokens=split, max_split_tokens=split)
+    bits = hp.host_bits(w)
+    out, plan = hp.run_hip(w, q_pos=pos, tuning=tuning)
+    ref, _, _ = hp.run_oracle(oracle_mod, w, bits=bits, q_pos=pos)
+    mx, mean = hp.check_close(out.float().cpu().numpy(), ref, what="explicit positions")
+    _say(f"explicit positions: items={plan.num_work_items()} merges={plan.num_merge_items()} max={mx:.2e} mean={mean:.2e}")
+    # the positions matter: the contiguous reading gives a different result on this input
+    ref_contig, _, _ = hp.run_oracle(oracle_mod, w, bits=bits)
+    assert np.abs(ref - ref_contig).max() > 1e-2
+    # contiguous positions through the same entry point reproduce the default path bit for bit
+    w2 = inputs.make_workload("obs_pos", seed=59, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                              page_size=16, block_size=B, prefix_len=L, chunk=c, block_inner=d_in,
+                              mask_mode=1, device=DEV)
+    contig = np.concatenate([np.arange(ci) + Li for Li, ci in zip(L, c)])
+    o_a, _ = hp.run_hip(w2, q_pos=contig, tuning=tuning)
+    w3 = inputs.make_workload("obs_pos", seed=59, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                              page_size=16, block_size=B, prefix_len=L, chunk=c, block_inner=d_in,
+                              mask_mode=1, device=DEV)
+    o_b, _ = hp.run_hip(w3, tuning=tuning)
+    assert torch.equal(o_a, o_b)
+
+
 def test_strided_interleaved_pool(oracle_mod):
     """K and V tiles interleaved in one allocation: page/head strides twice the dense ones."""
     _say("strided pool")
