@@ -408,6 +408,21 @@ def measure_selector(device: str):
             "samples_ms": [[int(s[0]), int(s[1]), int(s[2]), round(s[3], 4), round(s[4], 4)] for s in samples]}
 
 
+def copy_calibration(device: str):
+    """Three plain 1 GiB device copies: the known-size reference that scales the rocprofv3
+    FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    src = torch.empty(1 << 29, dtype=torch.bfloat16, device=device).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    out = {"bytes_read_per_copy": src.numel() * 2, "bytes_written_per_copy": src.numel() * 2, "copies": 3}
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
 def load_traffic(workload: str):
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
@@ -446,7 +461,10 @@ def main():
     if args.next_only:
         rows = {"commit": ("commit_step", measure_commit), "reorg": ("reorg_step", measure_reorg),
                 "selector": ("chunk_selector", measure_selector)}
-        print(json.dumps({"next_rows": {rows[k][0]: rows[k][1](dev) for k in args.next_rows.split(",")}}))
+        out = {"next_rows": {rows[k][0]: rows[k][1](dev) for k in args.next_rows.split(",")}}
+        if args.copy_calibration:
+            out["copy_calibration"] = copy_calibration(dev)
+        print(json.dumps(out))
         return
     cfg, chunk = parse_workload(args.workload)
     w, runner, res = measure(cfg, chunk, args.steps, args.warmup, dev)
@@ -478,15 +496,7 @@ def main():
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
-        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        line["copy_calibration"] = {"bytes_read_per_copy": src.numel() * 2,
-                                    "bytes_written_per_copy": src.numel() * 2, "copies": 3}
-        del src, dst
-        torch.cuda.empty_cache()
+        line["copy_calibration"] = copy_calibration(dev)
 
     if not args.no_others:
         others = []
