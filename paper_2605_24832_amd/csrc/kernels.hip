@@ -1247,8 +1247,8 @@ __global__ __launch_bounds__(256) void merge_kernel(KernelArgs a) {
 
 // KV append: chunk token j of request i -> logical slot L_i + j of the pool.  The planner cuts
 // every chunk into runs of up to 8 tokens whose slots lie in one aligned group of 8 slots (so
-// in one page).  Block = run; the threads walk all kv heads.  K: 16-byte groups per token.
-// V is slot-contiguous (stride P between d), so a run is written per (head, d) with the
+// in one page).  Block = (run, slice of 256 elements of the token row).  K: 16-byte groups per
+// token.  V is slot-contiguous (stride P between d), so a run is written per (head, d) with the
 // widest aligned stores that fit (16, 8, 4 or 2 bytes): a 2-byte store costs a whole 32-byte
 // memory write, which made the token-by-token version write 9x its payload.
 struct AppendRun { int32_t req, token0, slot0, count; };
@@ -1259,8 +1259,11 @@ struct PoolGeometry {
 };
 
 // Writes the `r.count` (1..8) tokens src[r.token0 ..] to the logical slots r.slot0.. of request
-// r.req; all of them lie in one aligned group of 8 slots.  A block-table entry outside the
-// pool writes nothing.
+// r.req; all of them lie in one aligned group of 8 slots.  The workgroup takes the 256 (head, d)
+// elements of a token row that start at element 256 * blockIdx.y: one V element column and at most
+// one 16-byte K piece per thread, so that a run is spread over Hkv * D / 256 workgroups (a
+// batch of one request has only c / 8 runs; one workgroup per run took 12 us there).  A
+// block-table entry outside the pool writes nothing.
 template <int D>
 __device__ __forceinline__ void write_run(uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool,
                                           const uint16_t* __restrict__ k_src, const uint16_t* __restrict__ v_src,
@@ -1270,19 +1273,25 @@ __device__ __forceinline__ void write_run(uint16_t* __restrict__ k_pool, uint16_
   if ((uint64_t)page >= (uint64_t)g.num_pages) return;   // uniform per block
   const int page_size = g.page_size;
   const int slot = r.slot0 & (page_size - 1);
-  const int64_t row = (int64_t)g.num_kv_heads * D;       // elements per token of the source
+  const int row_elems = g.num_kv_heads * D;              // elements per token of the source
+  const int64_t row = row_elems;
   const uint16_t* ksrc = k_src + (int64_t)r.token0 * row;
   const uint16_t* vsrc = v_src + (int64_t)r.token0 * row;
   uint16_t* kp = k_pool + page * g.k_stride_page;
   uint16_t* vp = v_pool + page * g.v_stride_page;
-  const int kpieces = g.num_kv_heads * (D / 8);
-  for (int e = threadIdx.x; e < r.count * kpieces; e += 256) {
-    const int j = e / kpieces, rem = e - j * kpieces;
-    const int h = rem / (D / 8), dg = rem % (D / 8);
-    const u32x4 x = *reinterpret_cast<const u32x4*>(ksrc + j * row + h * D + dg * 8);
-    *reinterpret_cast<u32x4*>(kp + (int64_t)h * g.k_stride_head + ((int64_t)dg * page_size + slot + j) * 8) = x;
+  const int e0 = (int)blockIdx.y * 256;                  // first (head, d) element of this workgroup
+  {
+    // K: token j, 16-byte piece q of the 32 pieces that cover elements e0 .. e0 + 255
+    const int j = threadIdx.x >> 5, q = threadIdx.x & 31;
+    const int el = e0 + q * 8;
+    if (j < r.count && el < row_elems) {
+      const int h = el / D, dg = (el % D) / 8;
+      const u32x4 x = *reinterpret_cast<const u32x4*>(ksrc + j * row + el);
+      *reinterpret_cast<u32x4*>(kp + (int64_t)h * g.k_stride_head + ((int64_t)dg * page_size + slot + j) * 8) = x;
+    }
   }
-  for (int e = threadIdx.x; e < g.num_kv_heads * D; e += 256) {
+  const int e = e0 + (int)threadIdx.x;
+  if (e < row_elems) {
     const int h = e / D, d = e % D;
     // w[p]: value for position p of the aligned group of 8 slots (register indices are
     // compile-time; first and count are the same for the whole block: no divergence)
@@ -1328,7 +1337,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   // copy, which is complete before the launch, not into the device copy being written.
   if ((int)blockIdx.x < upload_blocks) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < upload_n) upload_dst[i] = upload_src[i];
+    if (blockIdx.y == 0 && i < upload_n) upload_dst[i] = upload_src[i];
     return;
   }
   write_run<D>(k_pool, v_pool, k_new, v_new, block_table, runs[blockIdx.x - upload_blocks], g);
@@ -1437,7 +1446,7 @@ int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t*
   u32x4* ud = reinterpret_cast<u32x4*>(upload_dst);
   const u32x4* us = reinterpret_cast<const u32x4*>(upload_src);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  const dim3 grid(n_runs + up_blocks), block(256);
+  const dim3 grid(n_runs + up_blocks, (p.num_kv_heads * p.head_dim + 255) / 256), block(256);
   const AppendRun* r = reinterpret_cast<const AppendRun*>(runs);
   const PoolGeometry g = pool_geometry(p);
   if (p.head_dim == 128)
@@ -1457,7 +1466,7 @@ int launch_kv_write(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* 
   if (n <= 0) return OPTIMUS_OK;
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   const int groups = ((first_slot + n - 1) >> 3) - (first_slot >> 3) + 1;
-  const dim3 grid(groups), block(256);
+  const dim3 grid(groups, (p.num_kv_heads * p.head_dim + 255) / 256), block(256);
   const PoolGeometry g = pool_geometry(p);
   if (p.head_dim == 128)
     hipLaunchKernelGGL((kv_write_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_src, v_src,
