@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the chunked block-diffusion attention step on one MI355X.
 
-A step is one pass of the whole hot path over one synthetic batch: host planning
-(plan_update), KV append, attention forward, split-KV merge, all through the C ABI.
+A step is one pass of the whole hot path over one synthetic batch: host planning,
+KV append, attention forward, split-KV merge, all through the C ABI (optimus_attn_step).
 The inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others]
@@ -85,10 +85,13 @@ class Runner:
         kp, vp = self.pools[self.step_no % len(self.pools)]
         self.step_no += 1
         if replan:
-            # block-table validation is part of planning; the table itself is already on the device
-            self.plan.plan_update(w.cu_q, w.prefix_len, w.block_start, w.block_table)
-        self.plan.kv_append(kp, vp, w.k_new, w.v_new, self.bt)
-        self.plan.attn_forward(w.q, kp, vp, self.bt, self.out, self.ws)
+            # one library call per decoding iteration: planning (block-table validation is part of
+            # it; the table itself is already on the device), KV append, attention and merge
+            self.plan.attn_step(w.cu_q, w.prefix_len, w.block_start, w.block_table, w.q, w.k_new,
+                                w.v_new, kp, vp, self.bt, self.out, self.ws)
+        else:
+            self.plan.kv_append(kp, vp, w.k_new, w.v_new, self.bt)
+            self.plan.attn_forward(w.q, kp, vp, self.bt, self.out, self.ws)
 
     def timed(self, steps: int, warmup: int, replan: bool = True):
         """-> (ms per step wall, ms per step of the attention main kernel by HIP events)."""

@@ -177,6 +177,20 @@ int optimus_attn_forward_pos(optimus_attn_plan_t* plan, const void* q, const voi
                              const void* v_pool, const int32_t* block_table, const int32_t* q_pos,
                              void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* One decoding iteration in one call: optimus_attn_plan_update, optimus_kv_append and
+ * optimus_attn_forward_pos (Sec. 4.4: chunk sizes and cached lengths change every iteration, so
+ * planning is part of every step; Sec. 6 for the other two).  Same arguments, same launches and
+ * same results as the three calls; what it saves is two library calls and their argument
+ * marshalling, which count next to kernels of a few microseconds.  workspace_bytes is the
+ * capacity of `workspace`: if the new plan needs more, OPTIMUS_ERR_WORKSPACE_TOO_SMALL is
+ * returned after planning and nothing is launched (the split-KV partials need
+ * 4 x (D+2) bytes per query row and split).  q_pos may be NULL.                             */
+int optimus_attn_step(optimus_attn_plan_t* plan, int32_t batch, const int32_t* cu_q_host,
+                      const int32_t* prefix_len_host, const int32_t* block_start_host,
+                      const int32_t* block_table_host, const void* q, const void* k_new, const void* v_new,
+                      void* k_pool, void* v_pool, const int32_t* block_table, const int32_t* q_pos,
+                      void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* optimus_attn_forward for callers that cannot allocate or provide scratch memory: code under
  * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
  * same kernels and same results as optimus_attn_forward, except that the split-KV partials go

@@ -20,6 +20,7 @@ _lib = None
 EXPORTS = (
     "optimus_attn_plan_create", "optimus_attn_plan_update", "optimus_kv_append",
     "optimus_attn_forward", "optimus_attn_forward_pos", "optimus_attn_forward_static", "optimus_attn_static_scratch_bytes",
+    "optimus_attn_step",
     "optimus_attn_plan_destroy", "optimus_attn_plan_num_work_items",
     "optimus_attn_plan_num_merge_items", "optimus_attn_plan_get_work_items",
     "optimus_attn_plan_set_tuning", "optimus_attn_set_timing", "optimus_attn_timing_read",
@@ -93,6 +94,7 @@ def load_library():
         lib.optimus_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.optimus_attn_forward_pos.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.optimus_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        lib.optimus_attn_step.argtypes = [vp, i32] + [vp] * 13 + [ctypes.c_size_t, vp]
         lib.optimus_attn_static_scratch_bytes.argtypes = []
         lib.optimus_attn_static_scratch_bytes.restype = ctypes.c_size_t
         lib.optimus_attn_plan_destroy.argtypes = [vp]
@@ -290,6 +292,28 @@ class Plan:
                                                     _stream_ptr(stream))
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_forward")
+
+    def attn_step(self, cu_q, prefix_len, block_start, block_table_host, q, k_new, v_new, k_pool, v_pool,
+                  block_table, out, workspace=None, stream=None, q_pos=None) -> None:
+        """optimus_attn_step: plan_update, kv_append and attn_forward in one call (host descriptors
+        as for ``plan_update``; ``workspace`` must be large enough for the new plan)."""
+        cu, cu_p = _i32(cu_q)
+        pl, pl_p = _i32(prefix_len)
+        bs, bs_p = _i32(block_start)
+        if block_table_host is None:
+            bt_p = None
+        else:
+            bt, bt_p = _i32(block_table_host)
+        if len(cu) != len(pl) + 1 or len(bs) != len(pl):
+            raise ValueError("cu_q must have batch+1 entries, prefix_len and block_start batch")
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        rc = self._lib.optimus_attn_step(self._h, len(pl), cu_p, pl_p, bs_p, bt_p, _ptr(q), _ptr(k_new),
+                                         _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                         _ptr(q_pos), _ptr(out), _ptr(workspace), ws_bytes,
+                                         _stream_ptr(stream))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_step")
+        self.workspace_bytes = 0
 
     def attn_forward_static(self, q, k_pool, v_pool, block_table, out, stream=None) -> None:
         """optimus_attn_forward_static: the split-KV partials go to the library's static scratch."""

@@ -339,6 +339,23 @@ int optimus_attn_forward_pos(optimus_attn_plan_t* plan, const void* q, const voi
   return forward_impl(plan, q, k_pool, v_pool, block_table, q_pos, out, workspace, true, hip_stream);
 }
 
+int optimus_attn_step(optimus_attn_plan_t* plan, int32_t batch, const int32_t* cu_q_host,
+                      const int32_t* prefix_len_host, const int32_t* block_start_host,
+                      const int32_t* block_table_host, const void* q, const void* k_new, const void* v_new,
+                      void* k_pool, void* v_pool, const int32_t* block_table, const int32_t* q_pos,
+                      void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = optimus_attn_plan_update(plan, batch, cu_q_host, prefix_len_host, block_start_host,
+                                    block_table_host, nullptr);
+  if (rc != OPTIMUS_OK) return rc;
+  // nothing is launched when the workspace is too small for the new plan
+  if (plan->host.workspace_bytes > 0 && (!workspace || workspace_bytes < plan->host.workspace_bytes))
+    return OPTIMUS_ERR_WORKSPACE_TOO_SMALL;
+  rc = optimus_kv_append(plan, k_pool, v_pool, k_new, v_new, block_table, hip_stream);
+  if (rc != OPTIMUS_OK) return rc;
+  return optimus_attn_forward_pos(plan, q, k_pool, v_pool, block_table, q_pos, out, workspace,
+                                  workspace_bytes, hip_stream);
+}
+
 int optimus_attn_forward_static(optimus_attn_plan_t* plan, const void* q, const void* k_pool,
                                 const void* v_pool, const int32_t* block_table, void* out,
                                 void* hip_stream) {

@@ -21,8 +21,9 @@ def params_of_geometry(Hq, Hkv, D, P, B, num_pages, max_pages, **kw):
                       num_pages=num_pages, max_pages_per_req=max_pages, **kw)
 
 
-def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, q_pos=None, **kw):
-    """plan_update -> kv_append -> attn_forward on the workload's device tensors.
+def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, q_pos=None, step=False, **kw):
+    """plan_update -> kv_append -> attn_forward on the workload's device tensors
+    (``step=True``: after the sizing plan_update, one attn_step call does all three).
 
     Returns (out tensor on device, plan).  The pools of ``w`` are modified by the append.
     """
@@ -39,10 +40,14 @@ def run_hip(w, *, tuning=None, out_dtype=0, append=True, validate_table=True, q_
     ws.fill_(float("nan"))
     out = torch.full((w.total_q, w.num_q_heads, w.head_dim), float("nan"),
                      dtype=torch.float32 if out_dtype == 1 else torch.bfloat16, device=w.q.device)
-    if append:
-        plan.kv_append(w.k_pool, w.v_pool, w.k_new, w.v_new, bt)
     pos = None if q_pos is None else torch.as_tensor(np.asarray(q_pos, dtype=np.int32), device=w.q.device)
-    plan.attn_forward(w.q, w.k_pool, w.v_pool, bt, out, ws, q_pos=pos)
+    if step:
+        plan.attn_step(w.cu_q, w.prefix_len, w.block_start, w.block_table if validate_table else None,
+                       w.q, w.k_new, w.v_new, w.k_pool, w.v_pool, bt, out, ws, q_pos=pos)
+    else:
+        if append:
+            plan.kv_append(w.k_pool, w.v_pool, w.k_new, w.v_new, bt)
+        plan.attn_forward(w.q, w.k_pool, w.v_pool, bt, out, ws, q_pos=pos)
     torch.cuda.synchronize()
     return out, plan
 

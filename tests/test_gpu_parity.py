@@ -312,6 +312,34 @@ def test_append_overwrites_provisional_slots(oracle_mod):
     hp.check_close(out.float().cpu().numpy(), ref, what="overwrite")
 
 
+def test_one_call_step(oracle_mod):
+    """optimus_attn_step = plan_update + kv_append + attn_forward: same outputs and pool bytes as
+    the three calls (here: against the oracle), with explicit positions in the block-causal
+    mode, and the refusal of a workspace that is too small for the new plan."""
+    _say("one-call step")
+    kw = dict(seed=61, num_q_heads=28, num_kv_heads=4, head_dim=128, page_size=16, block_size=32,
+              prefix_len=[700, 90, 1500, 15, 333, 64, 4000], chunk=[1, 2, 4, 8, 16, 32, 5],
+              block_inner=[0] * 7, device=DEV)
+    w = inputs.make_workload("step", **kw)
+    _, plan = full_parity(oracle_mod, w, "step", step=True)
+    assert plan.num_merge_items() > 0
+    w = inputs.make_workload("step_obs", **dict(kw, mask_mode=1, chunk=[1, 2, 40, 8, 16, 70, 5]))
+    full_parity(oracle_mod, w, "step mask mode 1", step=True)
+    # too small a workspace: error after planning, nothing launched (the output stays poisoned)
+    w = inputs.make_workload("step", **kw)
+    p = hp.params_of(w)
+    from paper_2605_24832_amd import OptimusError, Plan
+    plan = Plan(p, device=0)
+    bt = torch.as_tensor(w.block_table, device=DEV)
+    out = torch.full_like(w.q, float("nan"))
+    with pytest.raises(OptimusError) as e:
+        plan.attn_step(w.cu_q, w.prefix_len, w.block_start, w.block_table, w.q, w.k_new, w.v_new,
+                       w.k_pool, w.v_pool, bt, out, torch.empty(4, dtype=torch.float32, device=DEV))
+    assert e.value.status == -8
+    torch.cuda.synchronize()
+    assert torch.isnan(out.float()).all()
+
+
 def test_empty_batches():
     _say("empty")
     w = inputs.make_workload("empty", seed=37, num_q_heads=8, num_kv_heads=2, head_dim=128,
