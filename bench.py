@@ -99,7 +99,9 @@ class Runner:
         for _ in range(warmup):
             self.step(replan)
         torch.cuda.synchronize()
-        self.plan.set_timing(True)
+        # the kernel of every 4th step is timed by the library's HIP events on this stream (timing
+        # every step would add 3 us of host work to steps that are 25 us long)
+        self.plan.set_timing(4)
         t0 = time.perf_counter()
         for _ in range(steps):
             self.step(replan)

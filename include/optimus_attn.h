@@ -228,11 +228,13 @@ int optimus_attn_plan_set_tuning(optimus_attn_plan_t* plan, int32_t target_items
                                  int32_t min_split_tokens, int32_t max_split_tokens);
 
 /* Optional timing of the attention main kernel with HIP events recorded on the
- * caller's stream around its launch(es) in every forward.  set_timing(enable
- * != 0) clears the record and turns recording on; timing_read synchronises on
- * the recorded events and returns the summed milliseconds and the number of
- * forwards recorded since then (at most 4096 are kept; later ones are dropped). */
-int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable);
+ * caller's stream around its launch.  set_timing(every): 0 turns recording off;
+ * n >= 1 clears the record and times the kernel of every n-th forward from now
+ * on (two event records cost the host about 3 us per timed forward, which
+ * shows in a step of 25 us: sample).  timing_read synchronises on the recorded
+ * events and returns the summed milliseconds and the number of forwards timed
+ * since then (at most 4096 are kept; later ones are dropped).                   */
+int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t every);
 int optimus_attn_timing_read(optimus_attn_plan_t* plan, float* total_ms_out,
                              int32_t* forwards_out);
 

@@ -322,13 +322,14 @@ class Plan:
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_forward_static")
 
-    def set_timing(self, enable: bool) -> None:
-        rc = self._lib.optimus_attn_set_timing(self._h, 1 if enable else 0)
+    def set_timing(self, every) -> None:
+        """0 / False: off; n (True = 1): time the attention kernel of every n-th forward."""
+        rc = self._lib.optimus_attn_set_timing(self._h, int(every))
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_set_timing")
 
     def timing_read(self):
-        """(summed attention-kernel milliseconds, forwards recorded) since set_timing(True)."""
+        """(summed attention-kernel milliseconds, forwards timed) since set_timing."""
         ms = ctypes.c_float(0)
         n = ctypes.c_int32(0)
         rc = self._lib.optimus_attn_timing_read(self._h, ctypes.byref(ms), ctypes.byref(n))

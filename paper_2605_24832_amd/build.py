@@ -28,6 +28,9 @@ def build(verbose: bool = False) -> str:
            # the lazy running-max test may be NaN, and either outcome of that compare keeps
            # -inf.  NaN in a visible input gives an undefined output, as in any attention kernel.
            "-fno-honor-nans",
+           # host code: SSE4.1 gives the planner's ceil() as one instruction instead of a
+           # library call (the work-list fit evaluates it a few thousand times per plan)
+           "-Xarch_host", "-msse4.1",
            "-Wall", "-Wno-unused-function",
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
     if verbose:

@@ -77,7 +77,8 @@ struct optimus_attn_plan {
 
   void* static_scratch = nullptr;  // this device's copy of the library's static scratch
 
-  bool timing = false;
+  int32_t timing_every = 0;      // 0 = off, n = the attention kernel of every n-th forward is timed
+  int64_t forwards_seen = 0;     // forwards since set_timing
   std::vector<hipEvent_t> events;  // pairs (start, stop), created on demand
   size_t events_used = 0;
 };
@@ -297,7 +298,9 @@ static int forward_impl(optimus_attn_plan_t* plan, const void* q, const void* k_
   a.scale_log2 = scale * 1.4426950408889634f;
 
   constexpr size_t kMaxTimedForwards = 4096;
-  const bool timed = allow_timing && plan->timing && plan->events_used < 2 * kMaxTimedForwards;
+  const bool timed = allow_timing && plan->timing_every > 0 &&
+                     plan->forwards_seen++ % plan->timing_every == 0 &&
+                     plan->events_used < 2 * kMaxTimedForwards;
   if (timed) {
     while (plan->events.size() < plan->events_used + 2) {
       hipEvent_t e;
@@ -411,10 +414,11 @@ int32_t optimus_attn_plan_get_work_items(const optimus_attn_plan_t* plan,
   return n;
 }
 
-int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t enable) {
-  if (!plan) return OPTIMUS_ERR_INVALID_ARGUMENT;
+int optimus_attn_set_timing(optimus_attn_plan_t* plan, int32_t every) {
+  if (!plan || every < 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
   if (plan->device < 0) return OPTIMUS_ERR_NO_DEVICE;
-  plan->timing = enable != 0;
+  plan->timing_every = every;
+  plan->forwards_seen = 0;
   plan->events_used = 0;
   return OPTIMUS_OK;
 }

@@ -235,12 +235,16 @@ int build_host_plan(const optimus_attn_params_t& p, const Tuning& tuning, int nu
   order.resize(groups.size());
   keys.resize(groups.size());
   uint32_t cost_max = 0;
+  bool sorted = true;   // already costliest first (a uniform batch): nothing to sort
   for (size_t k = 0; k < groups.size(); ++k) {
     keys[k] = (uint32_t)groups[k].cost10;
     cost_max = std::max(cost_max, (uint32_t)keys[k]);
+    sorted &= k == 0 || keys[k] <= keys[k - 1];
   }
   constexpr uint32_t kCountingLimit = 1u << 16;
-  if (cost_max < kCountingLimit) {
+  if (sorted) {
+    for (size_t k = 0; k < order.size(); ++k) order[k] = (int32_t)k;
+  } else if (cost_max < kCountingLimit) {
     std::vector<int32_t>& first = hp.scratch_count;   // first[b]: output position of bucket b
     first.assign((size_t)cost_max + 2, 0);
     for (size_t k = 0; k < groups.size(); ++k) ++first[cost_max - (uint32_t)keys[k] + 1];
