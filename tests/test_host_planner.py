@@ -88,6 +88,26 @@ def test_plan_update_error_codes():
     assert e.value.status == -10
 
 
+def test_one_call_step_reports_planning_errors_and_needs_a_device():
+    """optimus_attn_step plans first: descriptor errors come back as from plan_update, and a
+    host-only plan stops at the first device call (nothing is dereferenced before that)."""
+    plan = Plan(make_params(max_pages_per_req=8, num_pages=50), device=-1)
+    lib = binding.load_library()
+
+    def step(cu_q, prefix_len, block_start):
+        cu, pl, bs = (np.ascontiguousarray(a, dtype=np.int32) for a in (cu_q, prefix_len, block_start))
+        return lib.optimus_attn_step(plan._h, len(pl), cu.ctypes.data, pl.ctypes.data, bs.ctypes.data, None,
+                                     None, None, None, None, None, None, None, None, None, 0, None)
+
+    assert step([0, 4, 6], [60, 20], [32, 0]) == -10        # planned, then no device
+    assert plan.num_work_items() > 0
+    assert step([1, 4, 6], [60, 20], [32, 0]) == -3
+    assert step([0, 4, 6], [60, 20], [28, 0]) == -5
+    assert step([0, 4, 6], [60, 127], [32, 127]) == -6
+    assert lib.optimus_attn_step(None, 0, None, None, None, None, None, None, None, None, None, None,
+                                 None, None, None, 0, None) == -1
+
+
 def test_block_table_too_short_boundary():
     plan = Plan(make_params(max_pages_per_req=8), device=-1)
     plan.plan_update([0, 2], [126], [126])            # 128 slots = 8 pages: fits
