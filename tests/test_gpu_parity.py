@@ -129,6 +129,37 @@ def test_wide_rows_long_unsplit_key_range(oracle_mod, P):
     assert plan.num_merge_items() == 0
 
 
+@pytest.mark.parametrize("P", [16, 32, 64, 128])
+@pytest.mark.parametrize("D", [64, 128])
+def test_wide_only_batches(oracle_mod, D, P):
+    """Batches in which every (request, kv head) pair has more than 64 query rows, so that only
+    the wide body runs: key ranges of 1..8 tiles and longer (every prologue and tail case of its
+    staging ring), ragged row tiles (72, 104, 136 and 264 rows), an empty request in between;
+    default plan, forced splits, fp32 output and mask mode 1."""
+    _say(f"wide-only D={D} P={P}")
+    L = [0, 30, 70, 100, 140, 170, 200, 230, 50, 1000, 2077, 333]
+    c = [9, 9, 9, 9, 9, 9, 9, 9, 0, 13, 17, 33]
+    kw = dict(seed=300 + D + P, num_q_heads=16, num_kv_heads=2, head_dim=D, page_size=P,
+              block_size=64, prefix_len=L, chunk=c, block_inner=[0] * len(L), device=DEV)
+    # the smallest share of keys the planner gives an item grows with the rows of the largest
+    # pair (264 here), so only the two long requests can be split
+    split = dict(target_items=1 << 20, min_split_tokens=64, max_split_tokens=64)
+    for name, tuning in (("default", None), ("split", split)):
+        w = inputs.make_workload("wide_only", **kw)
+        _, plan = full_parity(oracle_mod, w, f"wide-only {name}", tuning=tuning)
+        assert plan.num_merge_items() > 0
+    w = inputs.make_workload("wide_only", **kw)
+    bits = hp.host_bits(w)
+    out, _ = hp.run_hip(w, out_dtype=1)
+    ref, _, _ = hp.run_oracle(oracle_mod, w, bits=bits)
+    mx, mean = hp.check_close(out.cpu().numpy(), ref, max_tol=5e-3, mean_tol=5e-4, what="wide-only fp32")
+    _say(f"wide-only fp32: max={mx:.2e} mean={mean:.2e}")
+    kw1 = dict(kw, block_size=32, block_inner=[0, 30, 6, 4, 12, 10, 8, 6, 18, 8, 29, 13], mask_mode=1)
+    for tuning in (None, split):
+        w = inputs.make_workload("wide_only_m1", **kw1)
+        full_parity(oracle_mod, w, "wide-only mask mode 1", tuning=tuning)
+
+
 def test_forced_splits_and_merge(oracle_mod):
     """Tiny split size: many partials per row, including splits some waves get no tile of."""
     _say("forced splits")
