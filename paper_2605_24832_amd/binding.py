@@ -205,6 +205,42 @@ def _stream_ptr(stream):
     return _raw_stream(torch.cuda.current_device())
 
 
+class HostBatch:
+    """The host descriptors of a batch, marshalled once: int32 arrays ``cu_q [batch+1]``,
+    ``prefix_len [batch]``, ``block_start [batch]`` and, optionally, ``block_table
+    [batch, max_pages_per_req]`` together with their addresses.  A decoding loop keeps one of
+    these and rewrites the arrays in place between iterations (the attributes are the arrays
+    the library reads), which takes the per-call conversions out of ``Plan.attn_step``."""
+
+    def __init__(self, cu_q, prefix_len, block_start, block_table=None):
+        self._cu_q = np.array(cu_q, dtype=np.int32, order="C")
+        self._prefix_len = np.array(prefix_len, dtype=np.int32, order="C")
+        self._block_start = np.array(block_start, dtype=np.int32, order="C")
+        self._block_table = None if block_table is None else np.array(block_table, dtype=np.int32, order="C")
+        if len(self._cu_q) != len(self._prefix_len) + 1 or len(self._block_start) != len(self._prefix_len):
+            raise ValueError("cu_q must have batch+1 entries, prefix_len and block_start batch")
+        self.batch = len(self._prefix_len)
+        self._p = (_i32(self._cu_q)[1], _i32(self._prefix_len)[1], _i32(self._block_start)[1],
+                   None if self._block_table is None else _i32(self._block_table)[1])
+
+    # read-only attributes: the arrays can be rewritten (``hb.cu_q[:] = ...``), not replaced
+    cu_q = property(lambda self: self._cu_q)
+    prefix_len = property(lambda self: self._prefix_len)
+    block_start = property(lambda self: self._block_start)
+    block_table = property(lambda self: self._block_table)
+
+
+class DeviceBuffers:
+    """The device tensors of ``Plan.attn_step`` resolved to addresses once (the tensors are kept
+    alive here): for loops that run every iteration on the same buffers."""
+
+    def __init__(self, q, k_new, v_new, k_pool, v_pool, block_table, out, workspace=None, q_pos=None):
+        self._keep = (q, k_new, v_new, k_pool, v_pool, block_table, out, workspace, q_pos)
+        self._p = (_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                   _ptr(q_pos), _ptr(out), _ptr(workspace))
+        self._ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+
+
 class Plan:
     """Owner of one ``optimus_attn_plan_t``; method names follow the C entry points."""
 
@@ -310,6 +346,17 @@ class Plan:
         rc = self._lib.optimus_attn_step(self._h, len(pl), cu_p, pl_p, bs_p, bt_p, _ptr(q), _ptr(k_new),
                                          _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
                                          _ptr(q_pos), _ptr(out), _ptr(workspace), ws_bytes,
+                                         _stream_ptr(stream))
+        if rc != 0:
+            raise OptimusError(rc, "optimus_attn_step")
+        self.workspace_bytes = 0
+
+    def attn_step_bound(self, host: HostBatch, dev: DeviceBuffers, stream=None) -> None:
+        """optimus_attn_step on descriptors and buffers marshalled beforehand (same call, same
+        checks in the library; only the per-call conversions of ``attn_step`` are gone)."""
+        h, d = host._p, dev._p
+        rc = self._lib.optimus_attn_step(self._h, host.batch, h[0], h[1], h[2], h[3], d[0], d[1], d[2],
+                                         d[3], d[4], d[5], d[6], d[7], d[8], dev._ws_bytes,
                                          _stream_ptr(stream))
         if rc != 0:
             raise OptimusError(rc, "optimus_attn_step")

@@ -371,6 +371,54 @@ def test_one_call_step(oracle_mod):
     assert torch.isnan(out.float()).all()
 
 
+def test_step_on_premarshalled_descriptors_and_buffers(oracle_mod):
+    """Plan.attn_step_bound (HostBatch + DeviceBuffers resolved once) is the same library call as
+    attn_step: equal outputs and pools bit for bit, and descriptors rewritten in place between
+    two iterations are what the second iteration uses (checked against the oracle)."""
+    _say("bound step")
+    from paper_2605_24832_amd import DeviceBuffers, HostBatch, Plan
+    kw = dict(seed=67, num_q_heads=16, num_kv_heads=2, head_dim=128, page_size=16, block_size=32,
+              device=DEV)
+    L1, c1 = [760, 90, 1500, 15], [1, 8, 4, 16]
+    L2, c2 = [701, 98, 1504, 31], [3, 2, 16, 1]          # same batch, other lengths and chunks
+    w1 = inputs.make_workload("bound", prefix_len=L1, chunk=c1, block_inner=[0] * 4,
+                              max_pages_per_req=100, **kw)
+    w2 = inputs.make_workload("bound", prefix_len=L2, chunk=c2, block_inner=[0] * 4,
+                              max_pages_per_req=100, **kw)
+    assert w2.num_pages <= w1.num_pages   # the plan is created for w1's pool
+    p = hp.params_of(w1)
+    plan = Plan(p, device=0)
+    ws = torch.empty(1 << 22, dtype=torch.float32, device=DEV)
+    host = HostBatch(w1.cu_q, w1.prefix_len, w1.block_start, w1.block_table)
+    # iteration 1 on w1's tensors
+    bits1 = hp.host_bits(w1)
+    out1 = torch.full_like(w1.q, float("nan"))
+    bt1 = torch.as_tensor(w1.block_table, device=DEV)
+    plan.attn_step_bound(host, DeviceBuffers(w1.q, w1.k_new, w1.v_new, w1.k_pool, w1.v_pool, bt1, out1, ws))
+    ref1, _, _ = hp.run_oracle(oracle_mod, w1, bits=bits1)
+    hp.check_close(out1.float().cpu().numpy(), ref1, what="bound step 1")
+    wa = inputs.make_workload("bound", prefix_len=L1, chunk=c1, block_inner=[0] * 4,
+                              max_pages_per_req=100, **kw)
+    out_a, _ = hp.run_hip(wa, step=True)
+    assert torch.equal(out1, out_a)
+    np.testing.assert_array_equal(inputs.to_bits(w1.k_pool), inputs.to_bits(wa.k_pool))   # NaN poison: bits
+    np.testing.assert_array_equal(inputs.to_bits(w1.v_pool), inputs.to_bits(wa.v_pool))
+    # iteration 2: the same HostBatch rewritten in place, w2's tensors
+    host.cu_q[:] = w2.cu_q
+    host.prefix_len[:] = w2.prefix_len
+    host.block_start[:] = w2.block_start
+    host.block_table[:] = w2.block_table
+    with pytest.raises(AttributeError):
+        host.cu_q = np.zeros(5, dtype=np.int32)
+    bits2 = hp.host_bits(w2)
+    out2 = torch.full_like(w2.q, float("nan"))
+    bt2 = torch.as_tensor(w2.block_table, device=DEV)
+    plan.attn_step_bound(host, DeviceBuffers(w2.q, w2.k_new, w2.v_new, w2.k_pool, w2.v_pool, bt2, out2, ws))
+    ref2, _, _ = hp.run_oracle(oracle_mod, w2, bits=bits2)
+    mx, mean = hp.check_close(out2.float().cpu().numpy(), ref2, what="bound step 2")
+    _say(f"bound step 2: max={mx:.2e} mean={mean:.2e}")
+
+
 def test_empty_batches():
     _say("empty")
     w = inputs.make_workload("empty", seed=37, num_q_heads=8, num_kv_heads=2, head_dim=128,

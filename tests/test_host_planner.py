@@ -356,3 +356,37 @@ def test_header_struct_sizes_match_binding():
     assert ctypes.sizeof(binding.WorkItem) == 32
     # 12 int32/float fields + 4 int64
     assert ctypes.sizeof(binding._CParams) == 12 * 4 + 4 * 8
+
+
+def test_host_batch_is_marshalled_once_and_rewritten_in_place():
+    """HostBatch copies the descriptors into int32 arrays whose addresses the library is given:
+    rewriting them in place changes what the next call plans, replacing them is refused, and
+    the one-call step on them reports planning errors like attn_step."""
+    from paper_2605_24832_amd import HostBatch
+    p = make_params()
+    hb = HostBatch([0, 4, 6], [100, 37], [96, 32])
+    assert hb.batch == 2 and hb.cu_q.dtype == np.int32 and hb.block_table is None
+    with pytest.raises(AttributeError):
+        hb.prefix_len = np.zeros(2, dtype=np.int32)
+    with pytest.raises(ValueError):
+        HostBatch([0, 4], [100, 37], [96, 32])
+    plan = Plan(p, device=-1)
+
+    class NoBuffers:   # a host-only plan stops before any device pointer is looked at
+        _p = (None,) * 9
+        _ws_bytes = 0
+    with pytest.raises(OptimusError) as e:
+        plan.attn_step_bound(hb, NoBuffers())
+    assert e.value.status == -10            # planned, then: no device
+    n0 = plan.num_work_items()
+    assert n0 > 0
+    hb.prefix_len[:] = [4000, 37]           # in place: a longer context, more items
+    hb.block_start[:] = [4000, 32]
+    with pytest.raises(OptimusError) as e:
+        plan.attn_step_bound(hb, NoBuffers())
+    # the longer context is split, and split items need a workspace: refused before any device call
+    assert e.value.status == -8 and plan.num_work_items() > n0
+    hb.cu_q[:] = [1, 4, 6]                  # in place: does not start at 0 any more
+    with pytest.raises(OptimusError) as e:
+        plan.attn_step_bound(hb, NoBuffers())
+    assert e.value.status == -3
