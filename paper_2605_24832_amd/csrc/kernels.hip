@@ -19,10 +19,10 @@
 //   slot-contiguous, makes every wave-wide load a contiguous run), each wave
 //   keeps its own online-softmax state and the waves are merged through LDS.
 //
-//   17..64 rows ("lds-tile" body): all waves walk the same tiles, staged once
+//   17..32 rows ("lds-tile" body): all waves walk the same tiles, staged once
 //   per workgroup in LDS, and each wave owns 16 of the rows.
 //
-//   pairs with more than 64 rows ("wide" body, further down): 32 rows per wave,
+//   pairs with more than 32 rows ("wide" body, further down): 32 rows per wave,
 //   32x32x16 MFMA, tiles loaded from global memory straight into LDS.
 //
 // Key ranges split over several work items leave partials that the merge
@@ -138,7 +138,7 @@ __device__ __forceinline__ TilePages tile_pages(const int32_t* __restrict__ bt, 
 }
 
 // Issue the loads of one 32-key tile whose page ids are already known.
-// K/V of the two narrow bodies are read exactly once per launch (a pair of at most 64 rows has
+// K/V of the two narrow bodies are read exactly once per launch (a pair of at most 32 rows has
 // a single row tile), so they are loaded with the non-temporal hint: measured 9 % faster on the
 // memory-bound configuration (853 -> 774 us, 6.56 TB/s) than plain loads, which let the
 // stream displace itself in the caches.  The wide body keeps plain loads: its sibling row
@@ -736,7 +736,7 @@ __device__ __forceinline__ void lds_tile_body(const KernelArgs& a, const optimus
 }
 
 // ---------------------------------------------------------------------------
-// attention kernel for the widest row tiles ("wide" body): 65..128 query rows.
+// attention kernel for the widest row tiles ("wide" body): 33..128 query rows.
 // Each wave owns 32 rows and both products use the 32x32x16 bf16 MFMA, whose
 // register layout (lane = 32*h + r, r 0..31, h 0..1) is
 //   A: row r, k = 8h..8h+7     B: col r, k = 8h..8h+7

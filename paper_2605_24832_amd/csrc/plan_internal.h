@@ -17,12 +17,15 @@ constexpr int kWavesPerBlock = 4;
 // rows is cut into row tiles of that many.  Pairs with more than kWideMinRows rows run the
 // wide body (32 rows per wave, all their row tiles, also a narrow last one); of the others,
 // items of at most 16 rows run the split-wave body (the waves split the keys) and items of
-// 17..64 rows the lds-tile body (the waves split the rows, 16 each).
+// 17..32 rows the lds-tile body (the waves split the rows, 16 each).  Measured on a mixed-chunk
+// batch: the wide body from 33 rows on is 3 % faster than from 65 on (waves without rows idle
+// there, but two waves then share every K/V operand read instead of four), from 17 on it is
+// 10 % slower on a batch of one 32-row request.
 constexpr int kMaxRowsPerItem = 128;
-constexpr int kWideMinRows = 64;
+constexpr int kWideMinRows = 32;
 constexpr int kNumXcd = 8;  // accelerator dies of an MI355X; workgroup i runs on die i % 8
 // Relative cost of one 32-key tile for an item of `rows` query rows (measured on 32K-key
-// scans: 16, 64 and 128 rows take 104, 114 and 113..128 us for the same key range).
+// scans: 16, 32..64 and 128 rows take 104, 114 and 113..128 us for the same key range).
 // In tenths, so that costs stay small integers.
 constexpr int tile_cost10_of_rows(int rows) { return rows <= 16 ? 10 : (rows <= kWideMinRows ? 11 : 12); }
 

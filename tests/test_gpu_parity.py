@@ -97,7 +97,7 @@ def test_gqa7_many_q_tiles(oracle_mod):
 
 @pytest.mark.parametrize("Hq,Hkv,D,P", [(12, 2, 128, 16), (32, 2, 64, 32), (16, 1, 128, 64), (24, 2, 64, 16)])
 def test_wide_row_tiles(oracle_mod, Hq, Hkv, D, P):
-    """Every lds-tile class: 33..64, 65..128, 129..192, 193..256 rows and more than 256 rows
+    """Every row-tile class of the wide body: 33..64, 65..128, 129..192, 193..256 rows and more than 256 rows
     (several row tiles), unsplit and split, with ragged key tails."""
     _say(f"wide rows Hq={Hq} Hkv={Hkv} D={D} P={P}")
     G = Hq // Hkv
@@ -132,7 +132,7 @@ def test_wide_rows_long_unsplit_key_range(oracle_mod, P):
 @pytest.mark.parametrize("P", [16, 32, 64, 128])
 @pytest.mark.parametrize("D", [64, 128])
 def test_wide_only_batches(oracle_mod, D, P):
-    """Batches in which every (request, kv head) pair has more than 64 query rows, so that only
+    """Batches in which every (request, kv head) pair has more than 32 query rows, so that only
     the wide body runs: key ranges of 1..8 tiles and longer (every prologue and tail case of its
     staging ring), ragged row tiles (72, 104, 136 and 264 rows), an empty request in between;
     default plan, forced splits, fp32 output and mask mode 1."""

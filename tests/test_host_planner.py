@@ -323,7 +323,7 @@ def test_plan_is_deterministic_and_longest_first_within_class():
     # widest row tile of its (request, kv head) pair
     G = p.num_q_heads // p.num_kv_heads
     widest = np.minimum(128, c[ia["req"]] * G)
-    tile_cost = np.where(widest <= 16, 1.0, np.where(widest <= 64, 1.1, 1.2))
+    tile_cost = np.where(widest <= 16, 1.0, np.where(widest <= 32, 1.1, 1.2))
     cost = ((ia["kv_end"] - ia["kv_begin"] + 31) // 32) * tile_cost
     # costliest first inside each of the 8 XCD lanes (workgroup i runs on XCD i % 8); checked on
     # the first half of the list, before the shortest lane can have run out
