@@ -227,15 +227,16 @@ int optimus_kv_append(optimus_attn_plan_t* plan, void* k_pool, void* v_pool, con
   const int n_runs = (int32_t)(plan->host.append_runs.size() / 4);
   if (!plan->dirty) {
     return launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
-                            (const uint16_t*)v_new, block_table, plan->dev_buf + plan->off_runs, n_runs,
-                            nullptr, nullptr, 0, hip_stream);
+                            (const uint16_t*)v_new, block_table, plan->dev_buf + plan->off_runs,
+                            plan->host.append_runs.data(), n_runs, nullptr, nullptr, 0, hip_stream);
   }
   // a work-list upload is pending: it rides in the same launch, and the runs are read from the
   // pinned copy
   const int sl = plan->slot;
   const int rc = launch_kv_append(plan->params, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)k_new,
-                        (const uint16_t*)v_new, block_table, plan->staging[sl] + plan->off_runs, n_runs,
-                        plan->dev_buf, plan->staging[sl], plan->upload_i32, hip_stream);
+                        (const uint16_t*)v_new, block_table, plan->staging[sl] + plan->off_runs,
+                        plan->host.append_runs.data(), n_runs, plan->dev_buf, plan->staging[sl],
+                        plan->upload_i32, hip_stream);
   if (rc != OPTIMUS_OK) return rc;
   OPT_HIP(hipEventRecord(plan->staging_done[sl], s), "hipEventRecord(staging)");
   plan->staging_busy[sl] = true;

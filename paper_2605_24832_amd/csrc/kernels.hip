@@ -34,6 +34,8 @@
 //   C/D: 4 floats, rows 4*kg .. 4*kg+3, col r
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include <mutex>
 
 #include "plan_internal.h"
@@ -1367,6 +1369,25 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   write_run<D>(k_pool, v_pool, k_new, v_new, block_table, runs[blockIdx.x - upload_blocks], g);
 }
 
+// The same with the runs in the kernel's argument block: a short list (a batch of a few dozen
+// requests) then reaches the workgroups with the launch itself, where reading it from the
+// pinned host copy costs every workgroup a trip over the host link before its first load.
+constexpr int kInlineRuns = 192;   // 3 KB of the 4 KB an argument block may have
+struct InlineRuns { AppendRun r[kInlineRuns]; };
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_inline_kernel(
+    uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const uint16_t* __restrict__ k_new,
+    const uint16_t* __restrict__ v_new, const int32_t* __restrict__ block_table, PoolGeometry g,
+    u32x4* __restrict__ upload_dst, const u32x4* __restrict__ upload_src, size_t upload_n,
+    int upload_blocks, InlineRuns runs) {
+  if ((int)blockIdx.x < upload_blocks) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.y == 0 && i < upload_n) upload_dst[i] = upload_src[i];
+    return;
+  }
+  write_run<D>(k_pool, v_pool, k_new, v_new, block_table, runs.r[blockIdx.x - upload_blocks], g);
+}
+
 // Plan-independent writer: tokens 0..n-1 of (k_src, v_src) go to the logical slots
 // first_slot.. of request `req`.  Block b takes the b-th aligned group of 8 slots the range touches.
 template <int D>
@@ -1461,7 +1482,7 @@ static PoolGeometry pool_geometry(const optimus_attn_params_t& p) {
 
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
-                     const int32_t* runs, int32_t n_runs, int32_t* upload_dst,
+                     const int32_t* runs, const int32_t* runs_host, int32_t n_runs, int32_t* upload_dst,
                      const int32_t* upload_src, size_t upload_i32, void* stream) {
   if (n_runs <= 0) return upload_i32 ? launch_upload(upload_dst, upload_src, upload_i32, stream) : OPTIMUS_OK;
   if (upload_i32 % 4 != 0) return OPTIMUS_ERR_INVALID_ARGUMENT;
@@ -1473,7 +1494,16 @@ int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t*
   const dim3 grid(n_runs + up_blocks, (p.num_kv_heads * p.head_dim + 255) / 256), block(256);
   const AppendRun* r = reinterpret_cast<const AppendRun*>(runs);
   const PoolGeometry g = pool_geometry(p);
-  if (p.head_dim == 128)
+  if (runs_host && n_runs <= kInlineRuns) {
+    InlineRuns in;
+    std::memcpy(in.r, runs_host, (size_t)n_runs * sizeof(AppendRun));
+    if (p.head_dim == 128)
+      hipLaunchKernelGGL((kv_append_inline_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
+                         block_table, g, ud, us, up_n, up_blocks, in);
+    else
+      hipLaunchKernelGGL((kv_append_inline_kernel<64>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
+                         block_table, g, ud, us, up_n, up_blocks, in);
+  } else if (p.head_dim == 128)
     hipLaunchKernelGGL((kv_append_kernel<128>), grid, block, 0, s, k_pool, v_pool, k_new, v_new,
                        block_table, r, g, ud, us, up_n, up_blocks);
   else

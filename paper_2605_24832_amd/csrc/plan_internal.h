@@ -115,11 +115,13 @@ int launch_attention(const optimus_attn_params_t& p, const KernelArgs& a, int32_
                      void* stream);
 int launch_merge(const optimus_attn_params_t& p, const KernelArgs& a, int32_t n_merges,
                  void* stream);
-// `runs` may live in pinned host memory.  If upload_i32 > 0 the launch also copies that many
-// int32 (a multiple of 4) from upload_src (pinned host) to upload_dst (device).
+// `runs` may live in pinned host memory; `runs_host` (optional) is the same list in ordinary
+// host memory, from which a short list is copied into the kernel's argument block.  If
+// upload_i32 > 0 the launch also copies that many int32 (a multiple of 4) from upload_src
+// (pinned host) to upload_dst (device).
 int launch_kv_append(const optimus_attn_params_t& p, uint16_t* k_pool, uint16_t* v_pool,
                      const uint16_t* k_new, const uint16_t* v_new, const int32_t* block_table,
-                     const int32_t* runs, int32_t n_runs, int32_t* upload_dst,
+                     const int32_t* runs, const int32_t* runs_host, int32_t n_runs, int32_t* upload_dst,
                      const int32_t* upload_src, size_t upload_i32, void* stream);
 
 // Tokens 0..n-1 of k_src / v_src ([n, Hkv, D]) -> logical slots first_slot.. of request `req`.
