@@ -419,6 +419,20 @@ def test_step_on_premarshalled_descriptors_and_buffers(oracle_mod):
     _say(f"bound step 2: max={mx:.2e} mean={mean:.2e}")
 
 
+@pytest.mark.parametrize("R", [191, 192, 193, 400])
+def test_append_run_list_in_the_argument_block_or_in_memory(oracle_mod, R):
+    """Up to 192 append runs travel in the kernel's argument block, longer lists are read from
+    memory: both sides of the limit (one run per request here), pools bit-exact, outputs to
+    the bar."""
+    _say(f"append runs R={R}")
+    rng = np.random.RandomState(R)
+    L = rng.randint(0, 200, size=R)
+    w = inputs.make_workload("runs", seed=500 + R, num_q_heads=4, num_kv_heads=2, head_dim=64,
+                             page_size=16, block_size=32, prefix_len=L, chunk=[1] * R,
+                             block_inner=L % 32, device=DEV)
+    full_parity(oracle_mod, w, f"append runs R={R}")
+
+
 def test_empty_batches():
     _say("empty")
     w = inputs.make_workload("empty", seed=37, num_q_heads=8, num_kv_heads=2, head_dim=128,
